@@ -1,0 +1,324 @@
+/*
+ * CPU oracle for the Insum SpMM hot path.  TEST INFRASTRUCTURE ONLY: nothing in the
+ * product (the HIP library and its Python binding) may include, link or call this file.
+ *
+ * Everything here is the plain definition from the paper, written as loops:
+ *   - indirect-Einsum semantics (output starts at zero, colliding writes are summed):
+ *     Section 3.1 "Extending Einsums with Indirect Indexing";
+ *   - GroupCOO and BlockGroupCOO (fixed-length groups along rows / block rows, the row
+ *     coordinate stored once per group, padding inside the last group of a row):
+ *     Section 4.1 "Grouping", the GroupCOO equation and the BlockCOO / BlockGroupCOO
+ *     figure captions;
+ *   - the indirect-access count F(g), its relaxation and g* = sqrt(S/n):
+ *     Section 4.2 "Choosing Group Size";
+ *   - the SpMM loops: the "GroupCOO SpMM" listing of the ablation study (Section 6.5)
+ *     and the BlockGroupCOO Einsum of Section 4.1.
+ *
+ * Where the paper is silent the oracle takes these readings (listed again in the
+ * design notes): entries are ordered by (row, column, input position); padding slots
+ * hold value +0 and repeat the column of the last real entry of their group; rows
+ * without entries produce no group; duplicate coordinates stay separate entries in
+ * GroupCOO and are an error in BlockGroupCOO; the default group size is the power of
+ * two nearest to g* in log2.
+ *
+ * Floating point: SpMM accumulates in fp64.  Inputs arrive as fp32 arrays that hold the
+ * (already rounded) fp32 / fp16 / bf16 values exactly.  Format conversion moves bytes
+ * and does no arithmetic on values.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------------------------ */
+/* canonical order                                                                       */
+/* ------------------------------------------------------------------------------------ */
+typedef struct {
+    int64_t key_hi; /* row (or block row)            */
+    int64_t key_lo; /* column (or block column, ...) */
+    int64_t pos;    /* input position: final tie-break */
+} sort_item;
+
+static int cmp_item(const void* a, const void* b) {
+    const sort_item* x = (const sort_item*)a;
+    const sort_item* y = (const sort_item*)b;
+    if (x->key_hi != y->key_hi) return x->key_hi < y->key_hi ? -1 : 1;
+    if (x->key_lo != y->key_lo) return x->key_lo < y->key_lo ? -1 : 1;
+    if (x->pos != y->pos) return x->pos < y->pos ? -1 : 1;
+    return 0;
+}
+
+/* perm[i] = input position of the i-th entry in (row, col, position) order.
+ * Returns 0, or 2 if a coordinate is outside [0,M) x [0,K). */
+int oracle_canonical_order(int64_t M, int64_t K, int64_t nnz, const int32_t* row,
+                           const int32_t* col, int64_t* perm) {
+    sort_item* it = (sort_item*)malloc(sizeof(sort_item) * (size_t)(nnz > 0 ? nnz : 1));
+    for (int64_t i = 0; i < nnz; ++i) {
+        if (row[i] < 0 || row[i] >= M || col[i] < 0 || col[i] >= K) {
+            free(it);
+            return 2;
+        }
+        it[i].key_hi = row[i];
+        it[i].key_lo = col[i];
+        it[i].pos = i;
+    }
+    qsort(it, (size_t)nnz, sizeof(sort_item), cmp_item);
+    for (int64_t i = 0; i < nnz; ++i) perm[i] = it[i].pos;
+    free(it);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* group size (Section 4.2)                                                               */
+/* ------------------------------------------------------------------------------------ */
+
+/* F(g) = (g + 1) * sum_i ceil(occ_i / g): scatters through AM plus gathers through AK. */
+int64_t oracle_indirect_access_cost(int64_t n, const int64_t* occ, int64_t g) {
+    int64_t groups = 0;
+    for (int64_t i = 0; i < n; ++i) groups += (occ[i] + g - 1) / g;
+    return (g + 1) * groups;
+}
+
+/* Relaxed cost with ceil(x) ~ x + 1:  S + S/g + n*g + n. */
+double oracle_relaxed_cost(double S, double n, double g) { return S + S / g + n * g + n; }
+
+/* Real-valued minimiser of the relaxed cost. */
+double oracle_gstar(double S, double n) { return sqrt(S / n); }
+
+/* Power of two nearest to g* in log2:  g = 2^e with e = round(log2(S/n) / 2), i.e. the
+ * e >= 0 with  n * 2^(2e-1) <= S < n * 2^(2e+1)  (e = 0 when S < 2n).  Integers only. */
+int64_t oracle_default_group_size(int64_t S, int64_t n) {
+    if (S <= 0 || n <= 0) return 1;
+    int e = 0;
+    while (e < 30) {
+        /* upper edge of the interval that rounds to e */
+        __int128 hi = (__int128)n << (2 * e + 1);
+        if ((__int128)S < hi) break;
+        ++e;
+    }
+    return (int64_t)1 << e;
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* COO -> GroupCOO (Section 4.1)                                                          */
+/* ------------------------------------------------------------------------------------ */
+
+/* occ[i] = entries in row i; returns G = sum_i ceil(occ_i / g). */
+int64_t oracle_groupcoo_num_groups(int64_t M, int64_t nnz, const int32_t* row, int64_t g,
+                                   int64_t* occ) {
+    for (int64_t i = 0; i < M; ++i) occ[i] = 0;
+    for (int64_t e = 0; e < nnz; ++e) occ[row[e]] += 1;
+    int64_t G = 0;
+    for (int64_t i = 0; i < M; ++i) G += (occ[i] + g - 1) / g;
+    return G;
+}
+
+/* Fills AM[G], AK[G*g], AV[G*g] (elem_size bytes per value, copied bit for bit).
+ * Returns 0 on success, 2 for an out-of-range coordinate. */
+int oracle_coo_to_groupcoo(int64_t M, int64_t K, int64_t nnz, const int32_t* row,
+                           const int32_t* col, const void* val, int elem_size, int64_t g,
+                           int32_t* AM, int32_t* AK, void* AV) {
+    int64_t* perm = (int64_t*)malloc(sizeof(int64_t) * (size_t)(nnz > 0 ? nnz : 1));
+    int rc = oracle_canonical_order(M, K, nnz, row, col, perm);
+    if (rc) {
+        free(perm);
+        return rc;
+    }
+    const char* vin = (const char*)val;
+    char* vout = (char*)AV;
+    int64_t p = 0; /* next group to emit */
+    int64_t e = 0; /* next sorted entry  */
+    while (e < nnz) {
+        const int32_t i = row[perm[e]];
+        int64_t end = e;
+        while (end < nnz && row[perm[end]] == i) ++end; /* entries e..end-1 form row i */
+        while (e < end) {
+            /* one group: up to g entries of row i, then padding */
+            AM[p] = i;
+            int32_t last_col = 0;
+            for (int64_t q = 0; q < g; ++q) {
+                if (e < end) {
+                    last_col = col[perm[e]];
+                    AK[p * g + q] = last_col;
+                    memcpy(vout + (size_t)(p * g + q) * elem_size,
+                           vin + (size_t)perm[e] * elem_size, (size_t)elem_size);
+                    ++e;
+                } else {
+                    AK[p * g + q] = last_col;                                   /* padding */
+                    memset(vout + (size_t)(p * g + q) * elem_size, 0, (size_t)elem_size); /* +0 */
+                }
+            }
+            ++p;
+        }
+    }
+    free(perm);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* COO -> BlockGroupCOO (Section 4.1, "Group+Blocking")                                   */
+/* ------------------------------------------------------------------------------------ */
+
+/* Sorted list of distinct nonzero blocks.  Returns 0, 2 (coordinate out of range),
+ * 3 (duplicate coordinate) or 5 (M or K not a multiple of the block shape).
+ * blk_row / blk_col must hold nnz entries; *num_blocks receives the count;
+ * occ[M/bM] receives the blocks per block row. */
+int oracle_nonzero_blocks(int64_t M, int64_t K, int64_t nnz, const int32_t* row,
+                          const int32_t* col, int64_t bM, int64_t bK, int64_t* num_blocks,
+                          int32_t* blk_row, int32_t* blk_col, int64_t* occ) {
+    if (bM <= 0 || bK <= 0 || M % bM || K % bK) return 5;
+    int64_t* perm = (int64_t*)malloc(sizeof(int64_t) * (size_t)(nnz > 0 ? nnz : 1));
+    int rc = oracle_canonical_order(M, K, nnz, row, col, perm);
+    if (rc) {
+        free(perm);
+        return rc;
+    }
+    for (int64_t e = 1; e < nnz; ++e)
+        if (row[perm[e]] == row[perm[e - 1]] && col[perm[e]] == col[perm[e - 1]]) {
+            free(perm);
+            return 3;
+        }
+    /* collect (block row, block col) of every entry, sort, keep distinct ones */
+    sort_item* it = (sort_item*)malloc(sizeof(sort_item) * (size_t)(nnz > 0 ? nnz : 1));
+    for (int64_t e = 0; e < nnz; ++e) {
+        it[e].key_hi = row[e] / bM;
+        it[e].key_lo = col[e] / bK;
+        it[e].pos = 0;
+    }
+    qsort(it, (size_t)nnz, sizeof(sort_item), cmp_item);
+    int64_t nb = 0;
+    for (int64_t i = 0; i < M / bM; ++i) occ[i] = 0;
+    for (int64_t e = 0; e < nnz; ++e) {
+        if (e == 0 || it[e].key_hi != it[e - 1].key_hi || it[e].key_lo != it[e - 1].key_lo) {
+            blk_row[nb] = (int32_t)it[e].key_hi;
+            blk_col[nb] = (int32_t)it[e].key_lo;
+            occ[it[e].key_hi] += 1;
+            ++nb;
+        }
+    }
+    *num_blocks = nb;
+    free(it);
+    free(perm);
+    return 0;
+}
+
+/* Fills AM[G], AK[G*g], AV[G*g*bM*bK] from the block list produced above (blocks sorted
+ * by (block row, block col)).  AV is zero-filled first; every input entry is then copied
+ * to its place inside its block. */
+int oracle_coo_to_blockgroupcoo(int64_t M, int64_t K, int64_t nnz, const int32_t* row,
+                                const int32_t* col, const void* val, int elem_size, int64_t bM,
+                                int64_t bK, int64_t g, int64_t num_blocks,
+                                const int32_t* blk_row, const int32_t* blk_col, int64_t G,
+                                int32_t* AM, int32_t* AK, void* AV) {
+    (void)M;
+    const int64_t nbc = K / bK;
+    const int64_t nbr = M / bM;
+    char* vout = (char*)AV;
+    const char* vin = (const char*)val;
+    memset(vout, 0, (size_t)(G * g * bM * bK) * elem_size);
+    /* slot_of[block row * nbc + block col] = flat slot p*g+q of that block, or -1 */
+    int64_t* slot_of = (int64_t*)malloc(sizeof(int64_t) * (size_t)(nbr * nbc > 0 ? nbr * nbc : 1));
+    for (int64_t i = 0; i < nbr * nbc; ++i) slot_of[i] = -1;
+    int64_t p = 0, b = 0;
+    while (b < num_blocks) {
+        const int32_t i = blk_row[b];
+        int64_t end = b;
+        while (end < num_blocks && blk_row[end] == i) ++end;
+        while (b < end) {
+            AM[p] = i;
+            int32_t last_col = 0;
+            for (int64_t q = 0; q < g; ++q) {
+                if (b < end) {
+                    last_col = blk_col[b];
+                    slot_of[(int64_t)i * nbc + last_col] = p * g + q;
+                    ++b;
+                }
+                AK[p * g + q] = last_col; /* real block column, or repeated for padding */
+            }
+            ++p;
+        }
+    }
+    if (p != G) {
+        free(slot_of);
+        return 4;
+    }
+    for (int64_t e = 0; e < nnz; ++e) {
+        const int64_t s = slot_of[(int64_t)(row[e] / bM) * nbc + col[e] / bK];
+        const int64_t off = ((s * bM + row[e] % bM) * bK + col[e] % bK);
+        memcpy(vout + (size_t)off * elem_size, vin + (size_t)e * elem_size, (size_t)elem_size);
+    }
+    free(slot_of);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* SpMM (fp64 accumulate)                                                                 */
+/* ------------------------------------------------------------------------------------ */
+
+static void column_slice(int64_t N, int64_t* n0, int64_t* n1) {
+#ifdef _OPENMP
+    const int t = omp_get_thread_num(), T = omp_get_num_threads();
+#else
+    const int t = 0, T = 1;
+#endif
+    *n0 = N * t / T;
+    *n1 = N * (t + 1) / T;
+}
+
+/* C[AM[p], n] += sum_q AV[p,q] * B[AK[p,q], n]   for every group p and column n.
+ * C is not cleared here: the caller passes zeros (plain Einsum) or the matrix to
+ * accumulate into.  Threads own disjoint column ranges, so there are no races and
+ * the summation order per output element is fixed. */
+void oracle_spmm_groupcoo(int64_t M, int64_t K, int64_t N, int64_t G, int64_t g,
+                          const int32_t* AM, const int32_t* AK, const float* AV,
+                          const float* B, int64_t ldb, double* C, int64_t ldc) {
+    (void)M;
+    (void)K;
+#pragma omp parallel
+    {
+        int64_t n0, n1;
+        column_slice(N, &n0, &n1);
+        for (int64_t p = 0; p < G; ++p) {
+            for (int64_t n = n0; n < n1; ++n) {
+                double acc = 0.0;
+                for (int64_t q = 0; q < g; ++q)
+                    acc += (double)AV[p * g + q] * (double)B[(int64_t)AK[p * g + q] * ldb + n];
+                C[(int64_t)AM[p] * ldc + n] += acc;
+            }
+        }
+    }
+}
+
+/* C[AM[p]*bM + bm, n] += sum_{q,bk} AV[p,q,bm,bk] * B[AK[p,q]*bK + bk, n]. */
+void oracle_spmm_blockgroupcoo(int64_t M, int64_t K, int64_t N, int64_t G, int64_t g,
+                               int64_t bM, int64_t bK, const int32_t* AM, const int32_t* AK,
+                               const float* AV, const float* B, int64_t ldb, double* C,
+                               int64_t ldc) {
+    (void)M;
+    (void)K;
+#pragma omp parallel
+    {
+        int64_t n0, n1;
+        column_slice(N, &n0, &n1);
+        for (int64_t p = 0; p < G; ++p)
+            for (int64_t q = 0; q < g; ++q)
+                for (int64_t bm = 0; bm < bM; ++bm)
+                    for (int64_t bk = 0; bk < bK; ++bk) {
+                        const double a = (double)AV[((p * g + q) * bM + bm) * bK + bk];
+                        const float* brow = B + ((int64_t)AK[p * g + q] * bK + bk) * ldb;
+                        double* crow = C + ((int64_t)AM[p] * bM + bm) * ldc;
+                        for (int64_t n = n0; n < n1; ++n) crow[n] += a * (double)brow[n];
+                    }
+    }
+}
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
