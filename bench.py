@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the Insum SpMM hot path on one MI355X.
+
+A step is one SpMM launch of the library (all kernels of the call) on a synthetic
+workload already resident in HBM; conversion to the fixed-length format happens once
+before the timed region and is reported separately.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--no-extra]
+
+The headline workload is cfg3 (GroupCOO, graph-aggregation shape, fp32, N = 128): the only
+configuration whose dense operand exceeds the on-chip caches, i.e. the one the HBM
+roofline applies to.  Unless --no-extra is given the line also carries the
+BlockGroupCOO result on cfg5 (MFMA roofline) and short results for the other configs.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_PEAK_TFLOPS = 2500.0      # dense bf16 / fp16
+SIZEOF = {"f32": 4, "f16": 2, "bf16": 2}
+
+
+def _torch_dtype(torch, name):
+    return {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[name]
+
+
+def _to_device(torch, x_f32, dtype):
+    import synth
+    st = synth.storage_array(x_f32, dtype)
+    if dtype == "bf16":
+        return torch.from_numpy(st.view(np.int16).copy()).view(torch.bfloat16).cuda()
+    return torch.from_numpy(st).cuda()
+
+
+def _time_launches(torch, fn, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(steps):
+        fn()
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) / steps      # ms per step
+
+
+def prepare(torch, I, name):
+    """Generate a workload, move it to the device and convert it with the library."""
+    import synth
+    cfg = synth.make_config(name)
+    row = torch.from_numpy(cfg["row"]).cuda()
+    col = torch.from_numpy(cfg["col"]).cuda()
+    val = _to_device(torch, cfg["val"], cfg["a_dtype"])
+    B = _to_device(torch, cfg["B"], cfg["b_dtype"])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    if cfg["kind"] == "group":
+        A = I.insum_coo_to_groupcoo(cfg["M"], cfg["K"], row, col, val, g=0)
+    else:
+        A = I.insum_coo_to_blockgroupcoo(cfg["M"], cfg["K"], row, col, val, cfg["bM"], cfg["bK"], g=0)
+    torch.cuda.synchronize()
+    conv_ms = (time.perf_counter() - t0) * 1e3
+    nnz = int(cfg["row"].shape[0])
+    del row, col, val
+    return cfg, A, B, nnz, conv_ms
+
+
+def run_workload(torch, I, name, steps, warmup):
+    cfg, A, B, nnz, conv_ms = prepare(torch, I, name)
+    M, N = cfg["M"], cfg["N"]
+    sA, sB, sC = SIZEOF[cfg["a_dtype"]], SIZEOF[cfg["b_dtype"]], SIZEOF[cfg["c_dtype"]]
+    C = torch.empty((M, N), dtype=_torch_dtype(torch, cfg["c_dtype"]), device="cuda")
+    if cfg["kind"] == "group":
+        ws = torch.empty(I.insum_spmm_groupcoo_workspace_bytes(M, N, A.G, A.g), dtype=torch.uint8,
+                         device="cuda")
+        fn = lambda: I.insum_spmm_groupcoo(A, B, C_out=C, workspace=ws)
+        slots = A.G * A.g
+        model_bytes = slots * (N * sB + 4 + sA) + 4 * A.G + M * N * sC
+        stored = slots
+    else:
+        fn = lambda: I.insum_spmm_blockgroupcoo(A, B, C_out=C)
+        nblk = nnz // (cfg["bM"] * cfg["bK"])
+        model_bytes = nblk * (cfg["bM"] * cfg["bK"] * sA + cfg["bK"] * N * sB) + 8 * A.G * A.g + M * N * sC
+        stored = nblk
+    ms = _time_launches(torch, fn, steps, warmup)
+    flops = 2.0 * nnz * N
+    res = {
+        "workload": name, "format": "GroupCOO" if cfg["kind"] == "group" else "BlockGroupCOO",
+        "M": M, "K": cfg["K"], "N": N, "nnz": nnz, "g": A.g, "groups": A.G, "stored_units": int(stored),
+        "dtype": cfg["a_dtype"], "ms_per_step": ms, "gflops": flops / ms / 1e6,
+        "model_bytes": int(model_bytes), "model_gbs": model_bytes / ms / 1e6,
+        "conversion_ms_incl_alloc": conv_ms,
+    }
+    if cfg["kind"] == "group":
+        res["roofline"] = {"bound": "hbm", "achieved": res["model_gbs"], "peak": HBM_PEAK_GBS,
+                           "unit": "GB/s", "frac": res["model_gbs"] / HBM_PEAK_GBS,
+                           "traffic": _traffic(name)}
+    else:
+        tf = flops / ms / 1e9
+        res["roofline"] = {"bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS,
+                           "unit": "TFLOP/s", "frac": tf / MFMA_PEAK_TFLOPS, "traffic": _traffic(name)}
+    return res, (cfg, A, B, C)
+
+
+def _traffic(name):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(name, {}).get("hbm_bytes_per_launch")
+    except (OSError, ValueError):
+        return None
+
+
+def cpu_baseline(cfg, A, nnz_total):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+    import oracle
+    from oracle import bf16_bits_to_f32
+    N = cfg["N"]
+    budget_fma = 1.5e9                          # roughly 10-30 s of oracle work
+    AM = A.AM.cpu().numpy()
+    G = AM.shape[0]
+    if cfg["kind"] == "group":
+        per_group = A.g * N
+    else:
+        per_group = A.g * cfg["bM"] * cfg["bK"] * N
+    Gs = int(min(G, max(1, budget_fma // per_group)))
+    AMs = AM[:Gs]
+    AKs = A.AK[:Gs].cpu().numpy()
+    AVt = A.AV[:Gs].cpu()
+    if cfg["a_dtype"] == "bf16":
+        import torch
+        AVs = bf16_bits_to_f32(AVt.view(torch.int16).numpy().view(np.uint16))
+    else:
+        AVs = AVt.numpy().astype(np.float32)
+    B = cfg["B"]
+    t0 = time.perf_counter()
+    if cfg["kind"] == "group":
+        oracle.spmm_groupcoo(cfg["M"], cfg["K"], N, AMs, AKs, AVs, B)
+        real = int(np.count_nonzero(AVs))       # padding holds exact zeros; values are nonzero
+    else:
+        oracle.spmm_blockgroupcoo(cfg["M"], cfg["K"], N, cfg["bM"], cfg["bK"], AMs, AKs, AVs, B)
+        real = int(np.count_nonzero(AVs))
+    dt = time.perf_counter() - t0
+    return {"value": 2.0 * real * N / dt / 1e9, "unit": "GFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": dt,
+            "sample": f"first {Gs} of {G} groups of {cfg['name']} ({real} nonzeros of {nnz_total}), "
+                      f"fp64 loops, includes zero-initialising the full C"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--no-extra", action="store_true", help="skip the other configs")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    import paper_2510_17505_amd as I
+
+    res, (cfg, A, B, C) = run_workload(torch, I, args.workload, args.steps, args.warmup)
+    line = {
+        "metric": "SpMM GFLOP/s (2*nnz*N)", "value": res["gflops"], "unit": "GFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg["a_dtype"], "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {res['format']} SpMM, A {cfg['M']}x{cfg['K']} "
+                               f"{cfg['a_dtype']} nnz={res['nnz']} g={res['g']}, B {cfg['K']}x{cfg['N']}",
+                   "format": res["format"], "g": res["g"], "groups": res["groups"]},
+        "roofline": res["roofline"],
+        "model_bytes_per_launch": res["model_bytes"],
+        "conversion_ms_incl_alloc": res["conversion_ms_incl_alloc"],
+    }
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(cfg, A, res["nnz"])
+    del A, B, C, cfg
+    torch.cuda.empty_cache()
+    if not args.no_extra:
+        others = {}
+        for name in ("cfg5", "cfg4", "cfg2", "cfg1"):
+            if name == args.workload:
+                continue
+            r, keep = run_workload(torch, I, name, args.steps, args.warmup)
+            del keep
+            torch.cuda.empty_cache()
+            others[name] = {k: r[k] for k in ("format", "dtype", "nnz", "N", "g", "ms_per_step", "gflops",
+                                              "model_gbs", "roofline", "conversion_ms_incl_alloc")}
+        line["other_workloads"] = others
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

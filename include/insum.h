@@ -1,0 +1,198 @@
+/*
+ * insum.h - C ABI of the MI355X (gfx950) library for sparse x dense matrix multiply
+ * written as an indirect Einsum over fixed-length sparse formats.
+ *
+ *     GroupCOO       C[AM[p], n]          += AV[p,q]       * B[AK[p,q], n]
+ *     BlockGroupCOO  C[AM[p]*bM + bm, n]  += AV[p,q,bm,bk] * B[AK[p,q]*bK + bk, n]
+ *
+ * (paper: Section 3.1 for the Einsum semantics, Section 4.1 for both formats and both
+ * Einsums, Section 4.2 for the group size, Section 6.5 for the GroupCOO SpMM loop.)
+ *
+ * Conventions that hold for every call unless a comment says otherwise
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are
+ *     ordinary host memory.  The library never frees anything and keeps no state
+ *     between calls.
+ *   - All matrices are row-major.  B is K x N with leading dimension ldb (elements),
+ *     C is M x N with leading dimension ldc.  Indices are int32; M, K, N, nnz < 2^31.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *     enqueued on it; SpMM calls never synchronise, conversion calls synchronise the
+ *     stream (they return counts to the host).
+ *   - Every function returns an insum_status and never throws or aborts.  After a
+ *     non-OK status the output buffers hold unspecified data.
+ */
+#ifndef INSUM_H
+#define INSUM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    INSUM_OK = 0,
+    INSUM_ERR_INVALID_ARG = 1,  /* null pointer, negative size, bad enum, misaligned    */
+    INSUM_ERR_OUT_OF_RANGE = 2, /* a coordinate lies outside [0,M) x [0,K)              */
+    INSUM_ERR_DUPLICATE = 3,    /* block conversion: the same (row, col) appears twice  */
+    INSUM_ERR_CAPACITY = 4,     /* an output or workspace buffer is too small           */
+    INSUM_ERR_UNSUPPORTED = 5,  /* dtype or shape combination that is not implemented   */
+    INSUM_ERR_HIP = 6           /* a HIP runtime call failed                            */
+} insum_status;
+
+typedef enum { INSUM_F32 = 0, INSUM_F16 = 1, INSUM_BF16 = 2 } insum_dtype;
+
+/* Library version (major*10000 + minor*100 + patch) and a static description of a
+ * status code.  Host only. */
+int insum_version(void);
+const char* insum_status_string(int status);
+
+/* ---------------------------------------------------------------------------------- */
+/* Group size (Section 4.2)                                                            */
+/* ---------------------------------------------------------------------------------- */
+
+/* Default group size: the power of two nearest (in log2) to g* = sqrt(S / n), where S
+ * is the number of stored entries (blocks for the block format) and n the number of
+ * rows (block rows), empty ones included.  Host only, integer arithmetic.  Returns 1
+ * when S <= 0 or n <= 0. */
+int32_t insum_default_group_size(int64_t S, int64_t n);
+
+/* F(g) = (g + 1) * sum_i ceil(occ_i / g): the number of indirect accesses (one scatter
+ * per group through AM, g gathers per group through AK).  `occ` is a host array of n
+ * row occupancies.  Returns -1 for invalid arguments. */
+int64_t insum_indirect_access_cost(int64_t n, const int64_t* occ, int32_t g);
+
+/* ---------------------------------------------------------------------------------- */
+/* COO -> GroupCOO (Section 4.1, "Grouping")                                           */
+/* ---------------------------------------------------------------------------------- */
+
+/* Bytes of device workspace the conversion below needs for a matrix with M rows and nnz
+ * entries.  Host only. */
+size_t insum_coo_to_groupcoo_workspace_bytes(int64_t M, int64_t nnz);
+
+/*
+ * Converts an element-wise COO matrix into GroupCOO with group size g.
+ *
+ *   row, col  device int32[nnz]   coordinates, any order, duplicates allowed (they stay
+ *                                 separate entries)
+ *   val       device dt[nnz]      values; copied bit for bit
+ *   g         group size, or 0 for insum_default_group_size(nnz, M)
+ *   g_used    host out            the group size that was used
+ *   num_groups host out           G = sum over rows of ceil(occ_row / g)
+ *   AM        device int32[capacity_groups]      row of each group (non-decreasing)
+ *   AK        device int32[capacity_groups * g]  columns, row-major [G, g]
+ *   AV        device dt[capacity_groups * g]     values,  row-major [G, g]
+ *   workspace device scratch of at least insum_coo_to_groupcoo_workspace_bytes(M, nnz)
+ *
+ * Layout produced: rows ascending; inside a row entries ascending by (column, input
+ * position); a row with occ entries owns ceil(occ/g) consecutive groups; only the last
+ * group of a row is padded, and a padding slot has value +0 and repeats the column of
+ * the last real entry of its group.  Rows without entries own no group.
+ *
+ * Count mode: pass AM = AK = AV = NULL (capacity_groups ignored) to obtain g_used and
+ * num_groups only.  Fill mode returns INSUM_ERR_CAPACITY, with num_groups set, when
+ * capacity_groups < G.  G never exceeds nnz/g + min(M, nnz).
+ * The call synchronises `stream` before it returns.
+ */
+insum_status insum_coo_to_groupcoo(int64_t M, int64_t K, int64_t nnz,
+                                   const int32_t* row, const int32_t* col, const void* val,
+                                   insum_dtype dt, int32_t g,
+                                   int32_t* g_used, int64_t* num_groups,
+                                   int32_t* AM, int32_t* AK, void* AV, int64_t capacity_groups,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------- */
+/* COO -> BlockGroupCOO (Section 4.1, "Group+Blocking")                                */
+/* ---------------------------------------------------------------------------------- */
+
+size_t insum_coo_to_blockgroupcoo_workspace_bytes(int64_t M, int64_t K, int64_t nnz,
+                                                  int32_t bM, int32_t bK);
+
+/*
+ * Converts an element-wise COO matrix into BlockGroupCOO with bM x bK blocks grouped
+ * along block rows.  Arguments as above, except:
+ *
+ *   bM, bK    block shape; M % bM == 0 and K % bK == 0 (else INSUM_ERR_UNSUPPORTED)
+ *   g         group size, or 0 for insum_default_group_size(#nonzero blocks, M / bM)
+ *   AM        device int32[capacity_groups]        block row of each group
+ *   AK        device int32[capacity_groups * g]    block columns [G, g]
+ *   AV        device dt[capacity_groups*g*bM*bK]   block values [G, g, bM, bK], bk fastest
+ *
+ * A block is stored when at least one input entry falls inside it (a zero-valued entry
+ * still counts); positions of a stored block without an entry hold +0.  Blocks are
+ * ordered by (block row, block column) and grouped like the entries of GroupCOO;
+ * padding blocks are all +0 and repeat the last real block column of their group.
+ * The same (row, col) given twice is INSUM_ERR_DUPLICATE.
+ * Count mode and capacity behaviour as for insum_coo_to_groupcoo.
+ */
+insum_status insum_coo_to_blockgroupcoo(int64_t M, int64_t K, int64_t nnz,
+                                        const int32_t* row, const int32_t* col, const void* val,
+                                        insum_dtype dt, int32_t bM, int32_t bK, int32_t g,
+                                        int32_t* g_used, int64_t* num_groups,
+                                        int32_t* AM, int32_t* AK, void* AV,
+                                        int64_t capacity_groups,
+                                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------- */
+/* SpMM over GroupCOO (Section 4.1 equation; loop nest of the Section 6.5 listing)     */
+/* ---------------------------------------------------------------------------------- */
+
+/* Bytes of device workspace insum_spmm_groupcoo needs (partial sums of rows whose groups
+ * are shared between two wavefront work ranges).  Host only. */
+size_t insum_spmm_groupcoo_workspace_bytes(int64_t M, int64_t N, int64_t G, int32_t g);
+
+/*
+ * C = A * B (accumulate == 0) or C += A * B (accumulate != 0), A given in GroupCOO.
+ *
+ *   AM, AK, AV  device; layout as produced by insum_coo_to_groupcoo.  AM must be
+ *               non-decreasing, 0 <= AM[p] < M, 0 <= AK[p,q] < K (not checked).
+ *   a_dt, b_dt, c_dt  supported: a_dt == b_dt in {F32, F16, BF16}; c_dt == b_dt or F32.
+ *               Products and sums are formed in fp32; C is rounded once
+ *               (round-to-nearest-even) when c_dt is a 16-bit type.
+ *   B           device b_dt[K, ldb];  C  device c_dt[M, ldc];  ldb, ldc >= N.
+ *   accumulate  0: every element of C[0:M, 0:N] is written (rows without groups become
+ *               zero); 1: existing C is read and added to.
+ *   workspace   device scratch, at least insum_spmm_groupcoo_workspace_bytes(...) bytes.
+ *
+ * B is assumed finite: a slot with value zero contributes nothing.  The result does not
+ * depend on run-to-run timing (no floating-point atomics are used).  Asynchronous.
+ */
+insum_status insum_spmm_groupcoo(int64_t M, int64_t K, int64_t N, int64_t G, int32_t g,
+                                 const int32_t* AM, const int32_t* AK, const void* AV,
+                                 insum_dtype a_dt,
+                                 const void* B, int64_t ldb, insum_dtype b_dt,
+                                 void* C, int64_t ldc, insum_dtype c_dt, int accumulate,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------- */
+/* SpMM over BlockGroupCOO (Section 4.1, BlockGroupCOO Einsum)                         */
+/* ---------------------------------------------------------------------------------- */
+
+size_t insum_spmm_blockgroupcoo_workspace_bytes(int64_t M, int64_t N, int64_t G, int32_t g,
+                                                int32_t bM, int32_t bK);
+
+/*
+ * C = A * B or C += A * B with A in BlockGroupCOO (layout as produced by
+ * insum_coo_to_blockgroupcoo; M % bM == 0, K % bK == 0).
+ *
+ *   a_dt == b_dt in {F16, BF16}; c_dt == b_dt or F32.  Products are exact, sums are
+ *   formed in fp32 on the matrix cores (MFMA) when bM is 32 or 64, bK is a multiple of 16
+ *   up to 128, N and ldb are multiples of 8 and B, AV are 16-byte aligned; other shapes
+ *   run on a slower general kernel with the same results up to summation order.
+ *   A padding block (one that repeats the previous block column of its group) is
+ *   skipped; B is assumed finite.
+ *
+ * Other arguments and behaviour as for insum_spmm_groupcoo.  Asynchronous.
+ */
+insum_status insum_spmm_blockgroupcoo(int64_t M, int64_t K, int64_t N, int64_t G, int32_t g,
+                                      int32_t bM, int32_t bK,
+                                      const int32_t* AM, const int32_t* AK, const void* AV,
+                                      insum_dtype a_dt,
+                                      const void* B, int64_t ldb, insum_dtype b_dt,
+                                      void* C, int64_t ldc, insum_dtype c_dt, int accumulate,
+                                      void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INSUM_H */

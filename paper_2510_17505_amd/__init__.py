@@ -1,0 +1,24 @@
+"""MI355X-native SpMM over the Insum fixed-length sparse formats (GroupCOO, BlockGroupCOO).
+
+Thin Python binding of ``libinsum.so``: the functions below only marshal arguments
+(device pointers of torch tensors, sizes, the current HIP stream) into the C ABI declared
+in ``include/insum.h``.  Every step of the computation runs in the library's HIP kernels;
+there is no CPU or PyTorch fallback, and importing this package fails if the library can
+neither be loaded nor built.
+"""
+from .api import (  # noqa: F401
+    BlockGroupCOO,
+    GroupCOO,
+    InsumError,
+    insum_coo_to_blockgroupcoo,
+    insum_coo_to_groupcoo,
+    insum_default_group_size,
+    insum_indirect_access_cost,
+    insum_spmm_blockgroupcoo,
+    insum_spmm_blockgroupcoo_workspace_bytes,
+    insum_spmm_groupcoo,
+    insum_spmm_groupcoo_workspace_bytes,
+    insum_status_string,
+    insum_version,
+    library_path,
+)

@@ -1,0 +1,223 @@
+"""ctypes binding of libinsum.so (see include/insum.h for the contract of every call)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+from . import _build
+
+_i64, _i32, _p = C.c_int64, C.c_int32, C.c_void_p
+
+OK, ERR_INVALID_ARG, ERR_OUT_OF_RANGE, ERR_DUPLICATE, ERR_CAPACITY, ERR_UNSUPPORTED, ERR_HIP = range(7)
+_DTYPE = {torch.float32: 0, torch.float16: 1, torch.bfloat16: 2}
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(_build.LIB):
+        _build.build()          # raises if hipcc is missing or compilation fails
+    return C.CDLL(_build.LIB)
+
+
+_lib = _load()
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def _sig(name, restype, argtypes):
+    fn = getattr(_lib, name)
+    fn.restype = restype
+    fn.argtypes = argtypes
+    return fn
+
+
+_version = _sig("insum_version", C.c_int, [])
+_status_string = _sig("insum_status_string", C.c_char_p, [C.c_int])
+_default_g = _sig("insum_default_group_size", _i32, [_i64, _i64])
+_cost = _sig("insum_indirect_access_cost", _i64, [_i64, _p, _i32])
+_g_ws = _sig("insum_coo_to_groupcoo_workspace_bytes", C.c_size_t, [_i64, _i64])
+_g_conv = _sig("insum_coo_to_groupcoo", C.c_int,
+               [_i64, _i64, _i64, _p, _p, _p, C.c_int, _i32, _p, _p, _p, _p, _p, _i64,
+                _p, C.c_size_t, _p])
+_b_ws = _sig("insum_coo_to_blockgroupcoo_workspace_bytes", C.c_size_t, [_i64, _i64, _i64, _i32, _i32])
+_b_conv = _sig("insum_coo_to_blockgroupcoo", C.c_int,
+               [_i64, _i64, _i64, _p, _p, _p, C.c_int, _i32, _i32, _i32, _p, _p, _p, _p, _p, _i64,
+                _p, C.c_size_t, _p])
+_sg_ws = _sig("insum_spmm_groupcoo_workspace_bytes", C.c_size_t, [_i64, _i64, _i64, _i32])
+_sg = _sig("insum_spmm_groupcoo", C.c_int,
+           [_i64, _i64, _i64, _i64, _i32, _p, _p, _p, C.c_int, _p, _i64, C.c_int,
+            _p, _i64, C.c_int, C.c_int, _p, C.c_size_t, _p])
+_sb_ws = _sig("insum_spmm_blockgroupcoo_workspace_bytes", C.c_size_t,
+              [_i64, _i64, _i64, _i32, _i32, _i32])
+_sb = _sig("insum_spmm_blockgroupcoo", C.c_int,
+           [_i64, _i64, _i64, _i64, _i32, _i32, _i32, _p, _p, _p, C.c_int, _p, _i64, C.c_int,
+            _p, _i64, C.c_int, C.c_int, _p, C.c_size_t, _p])
+
+
+class InsumError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        super().__init__(f"{where}: {insum_status_string(status)} (status {status})")
+        self.status = status
+
+
+def _check(status: int, where: str):
+    if status != OK:
+        raise InsumError(status, where)
+
+
+def _dev(t: torch.Tensor, name: str) -> torch.Tensor:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live in device memory")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t
+
+
+def _ptr(t) -> int:
+    return 0 if t is None or t.numel() == 0 else t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def insum_version() -> int:
+    return int(_version())
+
+
+def insum_status_string(status: int) -> str:
+    return _status_string(int(status)).decode()
+
+
+def insum_default_group_size(S: int, n: int) -> int:
+    return int(_default_g(int(S), int(n)))
+
+
+def insum_indirect_access_cost(occ, g: int) -> int:
+    arr = (C.c_int64 * len(occ))(*[int(x) for x in occ])
+    return int(_cost(len(occ), C.cast(arr, _p), int(g)))
+
+
+@dataclass
+class GroupCOO:
+    M: int
+    K: int
+    g: int
+    AM: torch.Tensor   # int32 [G]
+    AK: torch.Tensor   # int32 [G, g]
+    AV: torch.Tensor   # dtype [G, g]
+
+    @property
+    def G(self) -> int:
+        return int(self.AM.shape[0])
+
+
+@dataclass
+class BlockGroupCOO:
+    M: int
+    K: int
+    bM: int
+    bK: int
+    g: int
+    AM: torch.Tensor   # int32 [G]          block rows
+    AK: torch.Tensor   # int32 [G, g]       block columns
+    AV: torch.Tensor   # dtype [G, g, bM, bK]
+
+    @property
+    def G(self) -> int:
+        return int(self.AM.shape[0])
+
+
+def insum_coo_to_groupcoo(M: int, K: int, row, col, val, g: int = 0) -> GroupCOO:
+    row, col, val = _dev(row, "row"), _dev(col, "col"), _dev(val, "val")
+    assert row.dtype == torch.int32 and col.dtype == torch.int32 and val.dtype in _DTYPE
+    nnz = row.numel()
+    assert col.numel() == nnz and val.numel() == nnz
+    dev = val.device
+    ws = torch.empty(int(_g_ws(M, nnz)), dtype=torch.uint8, device=dev)
+    g_used, G = _i32(0), _i64(0)
+    args = (M, K, nnz, _ptr(row), _ptr(col), _ptr(val), _DTYPE[val.dtype], int(g),
+            C.addressof(g_used), C.addressof(G))
+    _check(_g_conv(*args, 0, 0, 0, 0, _ptr(ws), ws.numel(), _stream()), "insum_coo_to_groupcoo(count)")
+    AM = torch.empty(G.value, dtype=torch.int32, device=dev)
+    AK = torch.empty((G.value, g_used.value), dtype=torch.int32, device=dev)
+    AV = torch.empty((G.value, g_used.value), dtype=val.dtype, device=dev)
+    if G.value:
+        _check(_g_conv(*args, _ptr(AM), _ptr(AK), _ptr(AV), G.value, _ptr(ws), ws.numel(), _stream()),
+               "insum_coo_to_groupcoo(fill)")
+    return GroupCOO(M, K, g_used.value, AM, AK, AV)
+
+
+def insum_coo_to_blockgroupcoo(M: int, K: int, row, col, val, bM: int, bK: int, g: int = 0) -> BlockGroupCOO:
+    row, col, val = _dev(row, "row"), _dev(col, "col"), _dev(val, "val")
+    assert row.dtype == torch.int32 and col.dtype == torch.int32 and val.dtype in _DTYPE
+    nnz = row.numel()
+    assert col.numel() == nnz and val.numel() == nnz
+    dev = val.device
+    ws = torch.empty(int(_b_ws(M, K, nnz, bM, bK)), dtype=torch.uint8, device=dev)
+    g_used, G = _i32(0), _i64(0)
+    args = (M, K, nnz, _ptr(row), _ptr(col), _ptr(val), _DTYPE[val.dtype], int(bM), int(bK), int(g),
+            C.addressof(g_used), C.addressof(G))
+    _check(_b_conv(*args, 0, 0, 0, 0, _ptr(ws), ws.numel(), _stream()),
+           "insum_coo_to_blockgroupcoo(count)")
+    AM = torch.empty(G.value, dtype=torch.int32, device=dev)
+    AK = torch.empty((G.value, g_used.value), dtype=torch.int32, device=dev)
+    AV = torch.empty((G.value, g_used.value, bM, bK), dtype=val.dtype, device=dev)
+    if G.value:
+        _check(_b_conv(*args, _ptr(AM), _ptr(AK), _ptr(AV), G.value, _ptr(ws), ws.numel(), _stream()),
+               "insum_coo_to_blockgroupcoo(fill)")
+    return BlockGroupCOO(M, K, bM, bK, g_used.value, AM, AK, AV)
+
+
+def insum_spmm_groupcoo_workspace_bytes(M: int, N: int, G: int, g: int) -> int:
+    return int(_sg_ws(M, N, G, g))
+
+
+def insum_spmm_blockgroupcoo_workspace_bytes(M: int, N: int, G: int, g: int, bM: int, bK: int) -> int:
+    return int(_sb_ws(M, N, G, g, bM, bK))
+
+
+def _out(C_out, M, N, dtype, dev, accumulate):
+    if C_out is None:
+        if accumulate:
+            raise ValueError("accumulate=True needs an existing C")
+        C_out = torch.empty((M, N), dtype=dtype, device=dev)
+    assert C_out.is_cuda and C_out.dim() == 2 and C_out.shape == (M, N) and C_out.stride(1) == 1
+    return C_out
+
+
+def insum_spmm_groupcoo(A: GroupCOO, B: torch.Tensor, C_out: torch.Tensor | None = None,
+                        accumulate: bool = False, out_dtype=None, workspace=None) -> torch.Tensor:
+    """C = A @ B (or C += A @ B) with A in GroupCOO.  B: [K, N] row-major device tensor."""
+    assert B.is_cuda and B.dim() == 2 and B.shape[0] == A.K and B.stride(1) == 1
+    N = B.shape[1]
+    C_out = _out(C_out, A.M, N, out_dtype or B.dtype, B.device, accumulate)
+    if workspace is None:
+        workspace = torch.empty(insum_spmm_groupcoo_workspace_bytes(A.M, N, A.G, A.g),
+                                dtype=torch.uint8, device=B.device)
+    st = _sg(A.M, A.K, N, A.G, A.g, _ptr(A.AM), _ptr(A.AK), _ptr(A.AV), _DTYPE[A.AV.dtype],
+             _ptr(B), B.stride(0), _DTYPE[B.dtype], _ptr(C_out), C_out.stride(0),
+             _DTYPE[C_out.dtype], int(bool(accumulate)), _ptr(workspace), workspace.numel(), _stream())
+    _check(st, "insum_spmm_groupcoo")
+    return C_out
+
+
+def insum_spmm_blockgroupcoo(A: BlockGroupCOO, B: torch.Tensor, C_out: torch.Tensor | None = None,
+                             accumulate: bool = False, out_dtype=None, workspace=None) -> torch.Tensor:
+    """C = A @ B (or C += A @ B) with A in BlockGroupCOO."""
+    assert B.is_cuda and B.dim() == 2 and B.shape[0] == A.K and B.stride(1) == 1
+    N = B.shape[1]
+    C_out = _out(C_out, A.M, N, out_dtype or B.dtype, B.device, accumulate)
+    nws = insum_spmm_blockgroupcoo_workspace_bytes(A.M, N, A.G, A.g, A.bM, A.bK)
+    if workspace is None and nws:
+        workspace = torch.empty(nws, dtype=torch.uint8, device=B.device)
+    st = _sb(A.M, A.K, N, A.G, A.g, A.bM, A.bK, _ptr(A.AM), _ptr(A.AK), _ptr(A.AV),
+             _DTYPE[A.AV.dtype], _ptr(B), B.stride(0), _DTYPE[B.dtype], _ptr(C_out),
+             C_out.stride(0), _DTYPE[C_out.dtype], int(bool(accumulate)), _ptr(workspace),
+             0 if workspace is None else workspace.numel(), _stream())
+    _check(st, "insum_spmm_blockgroupcoo")
+    return C_out

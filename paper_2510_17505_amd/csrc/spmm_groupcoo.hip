@@ -1,0 +1,415 @@
+// SpMM over GroupCOO for gfx950:  C[AM[p], n] (+)= sum_q AV[p,q] * B[AK[p,q], n]
+// (paper: Section 4.1 GroupCOO equation; loop nest of the "GroupCOO SpMM" listing in
+// Section 6.5, which keeps the group's sum in a register and scatters once per group).
+//
+// Design (bandwidth-bound: every stored slot gathers one row of B)
+//   * The group list is cut into `runs` of equal length.  Because groups have a fixed
+//     number of slots, equal runs are equal work whatever the row-length distribution.
+//   * A run is owned by a "sub-wave": SW consecutive lanes of a wavefront, where SW lanes
+//     x 16 bytes cover one row of B (SW = 32 for N = 128 fp32 or N = 256 fp16).  A
+//     wavefront therefore gathers 64/SW rows per load instruction, each lane moving 16
+//     bytes, and no cross-lane reduction is needed for the products.
+//   * The run's slots are read with coalesced loads (lane j takes slot base+j: column,
+//     value and the row of its group) and handed to the other lanes with cross-lane
+//     shuffles, so the format is streamed exactly once.  B rows are fetched eight slots
+//     at a time before the first product is formed, which keeps 8 x 16 B per lane in
+//     flight.
+//   * Scatter is a segment reduction: AM is non-decreasing, so the sub-wave keeps the row
+//     sum in registers while the row does not change and stores it once.  Rows between
+//     two stored rows have no groups; the sub-wave that sees the jump writes their zeros,
+//     so C needs no separate clearing pass.
+//   * Rows cut by a run boundary: the piece at the head of a run and the piece at its
+//     tail go to an fp32 workspace; a second, tiny kernel adds the pieces of each such row
+//     in run order and writes the row once.  No floating-point atomics: results are
+//     reproducible, and 16-bit outputs are rounded exactly once.
+#include <algorithm>
+#include <initializer_list>
+
+#include "common.h"
+
+namespace insum {
+namespace {
+
+struct GroupParams {
+    int64_t M, N, G;
+    int32_t g, g_shift;  // g_shift = log2(g) when g is a power of two, else -1
+    const int32_t* AM;
+    const int32_t* AK;
+    const void* AV;
+    const void* B;
+    int64_t ldb;
+    void* C;
+    int64_t ldc;
+    int32_t accumulate;
+    int64_t runs, groups_per_run;
+    float* partial;  // [runs][2][npad]: 0 = head piece, 1 = tail piece
+    int64_t npad;
+};
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ inline int64_t imin(int64_t a, int64_t b) { return a < b ? a : b; }
+
+// Streaming (read-once) loads of format data.
+__device__ inline float load_stream(const float* p) { return __builtin_nontemporal_load(p); }
+__device__ inline float load_stream(const __half* p) {
+    const uint16_t u = __builtin_nontemporal_load(reinterpret_cast<const uint16_t*>(p));
+    return __half2float(__ushort_as_half(u));
+}
+__device__ inline float load_stream(const bf16_t* p) {
+    const uint16_t u = __builtin_nontemporal_load(reinterpret_cast<const uint16_t*>(p));
+    return __uint_as_float(((uint32_t)u) << 16);
+}
+
+// ---- 16-byte (or scalar) row pieces --------------------------------------------------
+template <typename T, int E>
+struct Piece;  // raw storage of E consecutive elements of type T
+
+template <>
+struct Piece<float, 4> {
+    f32x4 v;
+    __device__ void load(const float* p) { v = *reinterpret_cast<const f32x4*>(p); }
+    __device__ void zero() { v = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    __device__ void fma_into(float a, float (&acc)[4]) const {
+        acc[0] = fmaf(a, v.x, acc[0]);
+        acc[1] = fmaf(a, v.y, acc[1]);
+        acc[2] = fmaf(a, v.z, acc[2]);
+        acc[3] = fmaf(a, v.w, acc[3]);
+    }
+};
+template <>
+struct Piece<__half, 8> {
+    u32x4 v;
+    __device__ void load(const __half* p) { v = *reinterpret_cast<const u32x4*>(p); }
+    __device__ void zero() { v = u32x4{0, 0, 0, 0}; }
+    __device__ void fma_into(float a, float (&acc)[8]) const {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const __half2 h = *reinterpret_cast<const __half2*>(&w[i]);
+            const float2 f = __half22float2(h);
+            acc[2 * i] = fmaf(a, f.x, acc[2 * i]);
+            acc[2 * i + 1] = fmaf(a, f.y, acc[2 * i + 1]);
+        }
+    }
+};
+template <>
+struct Piece<bf16_t, 8> {
+    u32x4 v;
+    __device__ void load(const bf16_t* p) { v = *reinterpret_cast<const u32x4*>(p); }
+    __device__ void zero() { v = u32x4{0, 0, 0, 0}; }
+    __device__ void fma_into(float a, float (&acc)[8]) const {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            acc[2 * i] = fmaf(a, __uint_as_float(w[i] << 16), acc[2 * i]);
+            acc[2 * i + 1] = fmaf(a, __uint_as_float(w[i] & 0xffff0000u), acc[2 * i + 1]);
+        }
+    }
+};
+template <typename T>
+struct Piece<T, 1> {
+    T v;
+    __device__ void load(const T* p) { v = *p; }
+    __device__ void zero() { v = from_float<T>(0.f); }
+    __device__ void fma_into(float a, float (&acc)[1]) const { acc[0] = fmaf(a, to_float(v), acc[0]); }
+};
+
+// Write E fp32 sums to a row of C (converted to TC), optionally adding what is there.
+template <typename TC, int E>
+__device__ inline void store_c(TC* dst, const float (&acc)[E], bool add_old) {
+    float out[E];
+#pragma unroll
+    for (int i = 0; i < E; ++i) out[i] = acc[i];
+    if (add_old) {
+#pragma unroll
+        for (int i = 0; i < E; ++i) out[i] += to_float(dst[i]);
+    }
+    if constexpr (E == 1) {
+        dst[0] = from_float<TC>(out[0]);
+    } else if constexpr (sizeof(TC) == 4) {
+#pragma unroll
+        for (int i = 0; i < E; i += 4)
+            __builtin_nontemporal_store(f32x4{out[i], out[i + 1], out[i + 2], out[i + 3]},
+                                        reinterpret_cast<f32x4*>(dst + i));
+    } else {
+        static_assert(E == 8, "16-bit outputs use 8 elements per lane");
+        union {
+            TC h[8];
+            u32x4 u;
+        } pk;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) pk.h[i] = from_float<TC>(out[i]);
+        __builtin_nontemporal_store(pk.u, reinterpret_cast<u32x4*>(dst));
+    }
+}
+
+template <int E>
+__device__ inline void store_partial(float* dst, const float (&acc)[E]) {
+#pragma unroll
+    for (int i = 0; i < E; ++i) dst[i] = acc[i];
+}
+
+template <typename TC, int E>
+__device__ inline void zero_rows(TC* C, int64_t ldc, int64_t n0, int64_t first, int64_t last_excl) {
+    float z[E];
+#pragma unroll
+    for (int i = 0; i < E; ++i) z[i] = 0.f;
+    for (int64_t r = first; r < last_excl; ++r) store_c<TC, E>(C + r * ldc + n0, z, false);
+}
+
+__device__ inline int64_t group_of_slot(int64_t slot, int32_t g, int32_t g_shift) {
+    return g_shift >= 0 ? (slot >> g_shift) : (slot / g);
+}
+
+// ---- main kernel ---------------------------------------------------------------------
+template <typename TB, typename TC, int E, int SW>
+__global__ __launch_bounds__(256) void spmm_groupcoo_main(GroupParams p) {
+    constexpr int U = SW >= 8 ? 8 : SW;  // rows of B in flight per lane
+    const int lane = threadIdx.x % SW;
+    const int64_t run = ((int64_t)blockIdx.x * 256 + threadIdx.x) / SW;
+    if (run >= p.runs) return;  // the SW lanes of a sub-wave leave together
+    const int64_t n0 = ((int64_t)blockIdx.y * SW + lane) * E;
+    const bool col_ok = n0 < p.N;
+
+    const TB* __restrict__ B = static_cast<const TB*>(p.B);
+    const TB* __restrict__ AV = static_cast<const TB*>(p.AV);
+    const int32_t* __restrict__ AK = p.AK;
+    const int32_t* __restrict__ AM = p.AM;
+    TC* C = static_cast<TC*>(p.C);
+    const bool accumulate = p.accumulate != 0;
+
+    const int64_t gs = run * p.groups_per_run;
+    const int64_t ge = imin(p.G, gs + p.groups_per_run);
+    const int64_t slot_end = ge * p.g;
+    const int32_t first_row = AM[gs];
+    const int32_t prev_row = gs > 0 ? AM[gs - 1] : -1;
+    const int32_t last_row = AM[ge - 1];
+    const bool tail_cont = ge < p.G && AM[ge] == last_row;
+
+    float acc[E];
+#pragma unroll
+    for (int i = 0; i < E; ++i) acc[i] = 0.f;
+    int32_t cur = first_row;
+    bool cur_is_head = prev_row == first_row;  // this row began in an earlier run
+    float* const my_partial = p.partial + (run * 2) * p.npad + n0;
+
+    if (!accumulate && !cur_is_head && col_ok) zero_rows<TC, E>(C, p.ldc, n0, (int64_t)prev_row + 1, first_row);
+
+    for (int64_t sb = gs * p.g; sb < slot_end; sb += SW) {
+        // one coalesced read of the next SW slots of the format
+        const int64_t my = sb + lane;
+        const bool valid = my < slot_end;
+        int32_t ak_l = 0, am_l = 0;
+        float av_l = 0.f;
+        if (valid) {
+            ak_l = __builtin_nontemporal_load(AK + my);
+            av_l = load_stream(AV + my);
+            am_l = AM[group_of_slot(my, p.g, p.g_shift)];
+        }
+        const int nb = (int)imin((int64_t)SW, slot_end - sb);
+#pragma unroll
+        for (int c = 0; c < SW; c += U) {
+            if (c >= nb) break;
+            Piece<TB, E> rowpiece[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {  // gather: U rows of B, 16 bytes per lane each
+                const int32_t col = __shfl(ak_l, c + u, SW);
+                if (col_ok) rowpiece[u].load(B + (int64_t)col * p.ldb + n0);
+                else rowpiece[u].zero();
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (c + u < nb) {
+                    const int32_t r = __shfl(am_l, c + u, SW);
+                    const float a = __shfl(av_l, c + u, SW);
+                    if (r != cur) {  // segment boundary: the row sum is complete (in this run)
+                        if (col_ok) {
+                            if (cur_is_head) store_partial<E>(my_partial, acc);
+                            else store_c<TC, E>(C + (int64_t)cur * p.ldc + n0, acc, accumulate);
+                            if (!accumulate) zero_rows<TC, E>(C, p.ldc, n0, (int64_t)cur + 1, r);
+                        }
+                        cur_is_head = false;
+                        cur = r;
+#pragma unroll
+                        for (int i = 0; i < E; ++i) acc[i] = 0.f;
+                    }
+                    rowpiece[u].fma_into(a, acc);
+                }
+            }
+        }
+    }
+    if (col_ok) {
+        if (cur_is_head) store_partial<E>(my_partial, acc);
+        else if (tail_cont) store_partial<E>(my_partial + p.npad, acc);
+        else store_c<TC, E>(C + (int64_t)cur * p.ldc + n0, acc, accumulate);
+        if (ge == p.G && !accumulate) zero_rows<TC, E>(C, p.ldc, n0, (int64_t)cur + 1, p.M);
+    }
+}
+
+// ---- rows shared between runs ----------------------------------------------------------
+// Run r owns the row at its tail when that row starts inside r and continues into r+1.
+// Its sum is tail(r) + head(r+1) + head(r+2) + ... while the following runs still begin
+// with the same row.
+template <typename TC, int E, int SW>
+__global__ __launch_bounds__(256) void spmm_groupcoo_seams(GroupParams p) {
+    const int lane = threadIdx.x % SW;
+    const int64_t run = ((int64_t)blockIdx.x * 256 + threadIdx.x) / SW;
+    if (run >= p.runs) return;
+    const int64_t n0 = ((int64_t)blockIdx.y * SW + lane) * E;
+    if (n0 >= p.N) return;
+    const int32_t* __restrict__ AM = p.AM;
+    const int64_t gs = run * p.groups_per_run;
+    const int64_t ge = imin(p.G, gs + p.groups_per_run);
+    const int32_t row = AM[ge - 1];
+    if (!(ge < p.G && AM[ge] == row)) return;   // tail row ends here
+    if (gs > 0 && AM[gs - 1] == row) return;     // row began earlier: an earlier run owns it
+    float acc[E];
+    const float* tail = p.partial + (run * 2 + 1) * p.npad + n0;
+#pragma unroll
+    for (int i = 0; i < E; ++i) acc[i] = tail[i];
+    for (int64_t k = run + 1; k < p.runs; ++k) {
+        const float* head = p.partial + (k * 2) * p.npad + n0;
+#pragma unroll
+        for (int i = 0; i < E; ++i) acc[i] += head[i];
+        const int64_t ke = imin(p.G, (k + 1) * p.groups_per_run);
+        if (!(ke < p.G && AM[ke] == row)) break;
+    }
+    store_c<TC, E>(static_cast<TC*>(p.C) + (int64_t)row * p.ldc + n0, acc, p.accumulate != 0);
+}
+
+template <typename TC>
+__global__ __launch_bounds__(256) void fill_zero_2d(TC* C, int64_t ldc, int64_t M, int64_t N) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= M * N) return;
+    C[(i / N) * ldc + (i % N)] = static_cast<TC>(0);
+}
+
+// ---- launch planning -----------------------------------------------------------------
+struct Plan {
+    int E, SW;
+    int64_t col_tiles, groups_per_run, runs;
+};
+
+int next_pow2(int64_t x) {
+    int p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+
+// elem_size: bytes per element of B; vec: 16-byte path usable.
+Plan make_plan(int64_t N, int64_t G, int32_t g, int elem_size, bool vec) {
+    Plan pl;
+    pl.E = vec ? 16 / elem_size : 1;
+    const int64_t chunks = ceil_div(N, pl.E);
+    if (vec) {
+        pl.SW = (int)std::min<int64_t>(64, std::max<int64_t>(4, next_pow2(chunks)));
+    } else {
+        pl.SW = chunks <= 16 ? 16 : 64;
+    }
+    pl.col_tiles = ceil_div(chunks, pl.SW);
+    // About two runs per sub-wave slot of the chip (256 CUs x 32 wavefronts), but never
+    // fewer than two SW-slot batches per run.
+    const int64_t subwaves = 256LL * 32 * (64 / pl.SW);
+    const int64_t target_runs = std::max<int64_t>(1, 2 * subwaves / pl.col_tiles);
+    const int64_t min_groups = std::max<int64_t>(1, ceil_div(2 * pl.SW, g));
+    pl.groups_per_run = std::max<int64_t>(min_groups, ceil_div(G, target_runs));
+    pl.runs = G > 0 ? ceil_div(G, pl.groups_per_run) : 0;
+    return pl;
+}
+
+int64_t padded_cols(int64_t N) { return (N + 7) / 8 * 8; }
+
+template <typename TB, typename TC, int E, int SW>
+void launch_pair(const GroupParams& p, const Plan& pl, hipStream_t s) {
+    const dim3 grid((unsigned)ceil_div(p.runs, 256 / SW), (unsigned)pl.col_tiles);
+    hipLaunchKernelGGL((spmm_groupcoo_main<TB, TC, E, SW>), grid, dim3(256), 0, s, p);
+    hipLaunchKernelGGL((spmm_groupcoo_seams<TC, E, SW>), grid, dim3(256), 0, s, p);
+}
+
+template <typename TB, typename TC>
+void launch_typed(const GroupParams& p, const Plan& pl, hipStream_t s) {
+    constexpr int EV = 16 / (int)sizeof(TB);
+    if (pl.E == 1) {
+        if (pl.SW == 16) launch_pair<TB, TC, 1, 16>(p, pl, s);
+        else launch_pair<TB, TC, 1, 64>(p, pl, s);
+        return;
+    }
+    switch (pl.SW) {
+        case 4: launch_pair<TB, TC, EV, 4>(p, pl, s); break;
+        case 8: launch_pair<TB, TC, EV, 8>(p, pl, s); break;
+        case 16: launch_pair<TB, TC, EV, 16>(p, pl, s); break;
+        case 32: launch_pair<TB, TC, EV, 32>(p, pl, s); break;
+        default: launch_pair<TB, TC, EV, 64>(p, pl, s); break;
+    }
+}
+
+}  // namespace
+}  // namespace insum
+
+using namespace insum;
+
+extern "C" size_t insum_spmm_groupcoo_workspace_bytes(int64_t M, int64_t N, int64_t G, int32_t g) {
+    (void)M;
+    if (N <= 0 || G <= 0 || g <= 0) return 256;
+    int64_t runs = 0;
+    for (int es : {2, 4})
+        for (bool vec : {false, true}) runs = std::max(runs, make_plan(N, G, g, es, vec).runs);
+    return align_up((size_t)runs * 2 * (size_t)padded_cols(N) * sizeof(float), 256) + 256;
+}
+
+extern "C" insum_status insum_spmm_groupcoo(int64_t M, int64_t K, int64_t N, int64_t G, int32_t g,
+                                            const int32_t* AM, const int32_t* AK, const void* AV,
+                                            insum_dtype a_dt, const void* B, int64_t ldb,
+                                            insum_dtype b_dt, void* C, int64_t ldc,
+                                            insum_dtype c_dt, int accumulate, void* workspace,
+                                            size_t workspace_bytes, void* stream) {
+    if (M < 0 || K < 0 || N < 0 || G < 0 || g <= 0) return INSUM_ERR_INVALID_ARG;
+    if (M >= (1LL << 31) || K >= (1LL << 31) || N >= (1LL << 31)) return INSUM_ERR_INVALID_ARG;
+    if (!dtype_valid(a_dt) || !dtype_valid(b_dt) || !dtype_valid(c_dt)) return INSUM_ERR_INVALID_ARG;
+    if (a_dt != b_dt || (c_dt != b_dt && c_dt != INSUM_F32)) return INSUM_ERR_UNSUPPORTED;
+    if (ldb < N || ldc < N) return INSUM_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) return INSUM_OK;
+    if (!C) return INSUM_ERR_INVALID_ARG;
+    if (G > 0 && (!AM || !AK || !AV || !B || K == 0)) return INSUM_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    if (G == 0) {
+        if (!accumulate) {
+            const unsigned blocks = (unsigned)ceil_div(M * N, 256);
+            if (c_dt == INSUM_F32) hipLaunchKernelGGL(fill_zero_2d<float>, dim3(blocks), dim3(256), 0, s, (float*)C, ldc, M, N);
+            else hipLaunchKernelGGL(fill_zero_2d<uint16_t>, dim3(blocks), dim3(256), 0, s, (uint16_t*)C, ldc, M, N);
+            INSUM_HIP_TRY(hipGetLastError());
+        }
+        return INSUM_OK;
+    }
+
+    const int es = dtype_size(b_dt);
+    const int ev = 16 / es;
+    const bool vec = N % ev == 0 && ldb % ev == 0 && ldc % ev == 0 &&
+                     (reinterpret_cast<uintptr_t>(B) % 16) == 0 &&
+                     (reinterpret_cast<uintptr_t>(C) % 16) == 0;
+    const Plan pl = make_plan(N, G, g, es, vec);
+
+    GroupParams p;
+    p.M = M; p.N = N; p.G = G; p.g = g;
+    p.g_shift = (g & (g - 1)) == 0 ? __builtin_ctz((unsigned)g) : -1;
+    p.AM = AM; p.AK = AK; p.AV = AV; p.B = B; p.ldb = ldb; p.C = C; p.ldc = ldc;
+    p.accumulate = accumulate ? 1 : 0;
+    p.runs = pl.runs; p.groups_per_run = pl.groups_per_run;
+    p.npad = padded_cols(N);
+    const size_t need = (size_t)pl.runs * 2 * (size_t)p.npad * sizeof(float);
+    const uintptr_t ws = (reinterpret_cast<uintptr_t>(workspace) + 255) / 256 * 256;
+    if (!workspace || ws + need > reinterpret_cast<uintptr_t>(workspace) + workspace_bytes)
+        return INSUM_ERR_CAPACITY;
+    p.partial = reinterpret_cast<float*>(ws);
+
+    if (b_dt == INSUM_F32) launch_typed<float, float>(p, pl, s);
+    else if (b_dt == INSUM_F16 && c_dt == INSUM_F16) launch_typed<__half, __half>(p, pl, s);
+    else if (b_dt == INSUM_F16) launch_typed<__half, float>(p, pl, s);
+    else if (c_dt == INSUM_BF16) launch_typed<bf16_t, bf16_t>(p, pl, s);
+    else launch_typed<bf16_t, float>(p, pl, s);
+    INSUM_HIP_TRY(hipGetLastError());
+    return INSUM_OK;
+}

@@ -1,0 +1,315 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by
+element, on the same seeded inputs.  Conversion must match bit for bit; SpMM must stay
+within rtol = 1e-5 (fp32) / 2e-2 (fp16, bf16 with fp32 accumulation) of the fp64 oracle,
+both relative to max|C| and componentwise against (|A| |B|)."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from gpu_util import (RTOL, TORCH_DTYPE, assert_format_equal, coo_to_device, storage_to_torch,
+                      values_to_torch)
+from helpers import assert_spmm_close, to_f32
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def I():
+    import paper_2510_17505_amd as lib
+    assert torch.cuda.is_available()
+    return lib
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# --------------------------------------------------------------------------- #
+# conversion: bit exact
+# --------------------------------------------------------------------------- #
+GROUP_CASES = [
+    # M, K, nnz-ish, g, dtype, kind
+    (1, 1, 1, 1, "f32", "uniform"),
+    (5, 7, 12, 2, "f32", "uniform"),
+    (61, 45, 300, 3, "f16", "zipf"),
+    (512, 512, 2621, 0, "f32", "uniform"),
+    (1000, 777, 20000, 4, "bf16", "zipf"),
+    (3000, 5000, 60000, 16, "f16", "uniform"),
+    (4096, 64, 30000, 7, "f32", "dups"),
+    (20000, 30000, 250000, 0, "f32", "zipf"),
+    (300, 100000, 90000, 64, "f32", "hub"),
+]
+
+
+def _group_case(M, K, nnz, kind, dtype, seed):
+    if kind == "zipf":
+        row, col, val = synth.zipf_rows_coo(M, K, 1.2, max(1.0, nnz / M), seed, dtype, "normal")
+    else:
+        row, col, val = synth.random_coo(M, K, nnz, seed, dtype)
+    if kind == "dups":      # duplicate coordinates and explicit zeros
+        row = np.concatenate([row, row[:500]])
+        col = np.concatenate([col, col[:500]])
+        val = np.concatenate([val, -val[:500]])
+        val[::13] = 0.0
+    if kind == "hub":       # one very long row, many empty rows
+        keep = row % 7 == 0
+        extra = np.arange(0, K, 3, dtype=np.int32)
+        row = np.concatenate([row[keep], np.full(extra.size, 123, np.int32)])
+        col = np.concatenate([col[keep], extra])
+        val = synth.round_to_dtype(np.random.default_rng(seed).standard_normal(row.size), dtype)
+        perm = np.random.default_rng(seed + 1).permutation(row.size)
+        row, col, val = row[perm], col[perm], val[perm]
+    return row, col, val
+
+
+@pytest.mark.parametrize("M,K,nnz,g,dtype,kind", GROUP_CASES)
+def test_coo_to_groupcoo_bit_exact(I, M, K, nnz, g, dtype, kind):
+    _say(f"[groupcoo convert] M={M} K={K} nnz~{nnz} g={g} {dtype} {kind}")
+    row, col, val = _group_case(M, K, nnz, kind, dtype, seed=nnz)
+    want = oracle.coo_to_groupcoo(M, K, row, col, synth.storage_array(val, dtype), g or None)
+    got = I.insum_coo_to_groupcoo(M, K, *coo_to_device(row, col, val, dtype), g=g)
+    assert_format_equal(got.g, got.AM, got.AK, got.AV, want)
+    # same call twice gives the same bits (no dependence on atomics' order)
+    again = I.insum_coo_to_groupcoo(M, K, *coo_to_device(row, col, val, dtype), g=g)
+    assert torch.equal(again.AK, got.AK) and torch.equal(again.AM, got.AM)
+
+
+def test_coo_to_groupcoo_edge_cases(I):
+    dev = "cuda"
+    e = torch.zeros(0, dtype=torch.int32, device=dev)
+    f = I.insum_coo_to_groupcoo(10, 10, e, e, torch.zeros(0, device=dev), g=4)
+    assert f.G == 0 and f.g == 4
+    f = I.insum_coo_to_groupcoo(10, 10, e, e, torch.zeros(0, device=dev), g=0)
+    assert f.g == 1
+    row = torch.tensor([0, 10], dtype=torch.int32, device=dev)
+    col = torch.tensor([0, 0], dtype=torch.int32, device=dev)
+    with pytest.raises(I.InsumError) as ex:
+        I.insum_coo_to_groupcoo(10, 10, row, col, torch.ones(2, device=dev), g=2)
+    assert ex.value.status == 2
+    with pytest.raises(I.InsumError) as ex:
+        I.insum_coo_to_groupcoo(10, 10, col, row - 11, torch.ones(2, device=dev), g=2)
+    assert ex.value.status == 2
+
+
+BLOCK_CASES = [
+    # M, K, bM, bK, g, dtype, density, fill
+    (64, 64, 32, 32, 1, "bf16", 0.5, 1.0),
+    (256, 384, 32, 32, 4, "bf16", 0.3, 1.0),
+    (512, 256, 64, 64, 0, "f16", 0.4, 0.6),
+    (96, 160, 8, 16, 3, "f32", 0.3, 0.5),
+    (120, 90, 4, 2, 2, "f16", 0.2, 0.9),
+    (2048, 2048, 32, 32, 0, "bf16", 0.1, 1.0),
+    (50, 70, 1, 1, 4, "f32", 0.1, 1.0),
+]
+
+
+@pytest.mark.parametrize("M,K,bM,bK,g,dtype,density,fill", BLOCK_CASES)
+def test_coo_to_blockgroupcoo_bit_exact(I, M, K, bM, bK, g, dtype, density, fill):
+    _say(f"[blockgroupcoo convert] M={M} K={K} b={bM}x{bK} g={g} {dtype}")
+    row, col, val = synth.random_block_coo(M, K, bM, bK, seed=M + bK, dtype=dtype,
+                                           block_density=density, fill=fill)
+    want = oracle.coo_to_blockgroupcoo(M, K, row, col, synth.storage_array(val, dtype), bM, bK, g or None)
+    got = I.insum_coo_to_blockgroupcoo(M, K, *coo_to_device(row, col, val, dtype), bM, bK, g=g)
+    assert_format_equal(got.g, got.AM, got.AK, got.AV, want)
+
+
+def test_coo_to_blockgroupcoo_zipf_rows_and_errors(I):
+    M = K = 1024
+    row, col, val = synth.random_block_coo(M, K, 64, 64, seed=5, dtype="bf16", zipf_alpha=1.0,
+                                           zipf_mean=4.0)
+    want = oracle.coo_to_blockgroupcoo(M, K, row, col, synth.storage_array(val, "bf16"), 64, 64, None)
+    got = I.insum_coo_to_blockgroupcoo(M, K, *coo_to_device(row, col, val, "bf16"), 64, 64, g=0)
+    assert_format_equal(got.g, got.AM, got.AK, got.AV, want)
+    r, c, v = coo_to_device(np.array([1, 1, 5]), np.array([2, 2, 3]), np.ones(3, np.float32), "f32")
+    with pytest.raises(I.InsumError) as ex:
+        I.insum_coo_to_blockgroupcoo(8, 8, r, c, v, 2, 2, g=1)
+    assert ex.value.status == 3          # duplicate
+    with pytest.raises(I.InsumError) as ex:
+        I.insum_coo_to_blockgroupcoo(9, 8, r, c, v, 2, 2, g=1)
+    assert ex.value.status == 5          # not divisible
+    r2 = torch.tensor([1, 8], dtype=torch.int32, device="cuda")
+    with pytest.raises(I.InsumError) as ex:
+        I.insum_coo_to_blockgroupcoo(8, 8, r2, c[:2], v[:2], 2, 2, g=1)
+    assert ex.value.status == 2          # out of range
+
+
+# --------------------------------------------------------------------------- #
+# SpMM over GroupCOO
+# --------------------------------------------------------------------------- #
+def _oracle_group_spmm(M, K, N, fmt, dtype, B, C0=None):
+    g, AM, AK, AV = fmt
+    av = to_f32(AV, dtype)
+    C64 = oracle.spmm_groupcoo(M, K, N, AM, AK, av, B, C_init=C0)
+    absprod = oracle.spmm_groupcoo(M, K, N, AM, AK, np.abs(av), np.abs(B),
+                                   C_init=None if C0 is None else np.abs(C0))
+    return C64, absprod
+
+
+def _gpu_group_format(I, M, K, fmt, dtype):
+    g, AM, AK, AV = fmt
+    return I.GroupCOO(M, K, g, torch.from_numpy(AM).cuda(), torch.from_numpy(AK).cuda(),
+                      storage_to_torch(AV, dtype))
+
+
+SPMM_GROUP_CASES = [
+    # M, K, N, nnz, g, dtype, kind
+    (37, 53, 9, 300, 2, "f32", "uniform"),        # scalar path, N < 16
+    (37, 53, 1, 300, 4, "f32", "uniform"),
+    (200, 300, 100, 3000, 3, "f32", "uniform"),   # g not a power of two
+    (512, 512, 64, 2621, 2, "f32", "uniform"),    # cfg1 shape
+    (3000, 2000, 128, 50000, 4, "f32", "zipf"),   # cfg3 shape, several runs
+    (3000, 2000, 130, 50000, 4, "f32", "zipf"),   # N not a multiple of 4 -> scalar path
+    (3000, 2000, 132, 50000, 8, "f32", "zipf"),   # ragged last lanes
+    (1000, 4096, 256, 100000, 16, "f16", "uniform"),   # cfg2 shape
+    (1000, 4096, 256, 100000, 16, "bf16", "uniform"),
+    (1000, 1000, 600, 20000, 4, "f32", "uniform"),     # two column tiles
+    (1000, 1000, 1032, 20000, 1, "f16", "uniform"),    # g = 1 (COO), three column tiles
+    (300, 100000, 128, 90000, 4, "f32", "hub"),        # one row spanning many runs
+    (300, 100000, 64, 90000, 32, "f16", "hub"),
+    (5000, 5000, 32, 4000, 4, "f32", "uniform"),       # mostly empty rows
+    (64, 64, 24, 4096, 64, "bf16", "uniform"),         # dense matrix, g = row length
+]
+
+
+@pytest.mark.parametrize("M,K,N,nnz,g,dtype,kind", SPMM_GROUP_CASES)
+def test_spmm_groupcoo_parity(I, M, K, N, nnz, g, dtype, kind):
+    _say(f"[spmm groupcoo] M={M} K={K} N={N} nnz~{nnz} g={g} {dtype} {kind}")
+    row, col, val = _group_case(M, K, nnz, kind, dtype, seed=N + g)
+    fmt = oracle.coo_to_groupcoo(M, K, row, col, synth.storage_array(val, dtype), g)
+    B = synth.round_to_dtype(np.random.default_rng(N).standard_normal((K, N)), dtype)
+    C64, absprod = _oracle_group_spmm(M, K, N, fmt, dtype, B)
+    A = _gpu_group_format(I, M, K, fmt, dtype)
+    Bd = values_to_torch(B, dtype)
+    C = I.insum_spmm_groupcoo(A, Bd)
+    assert C.dtype == TORCH_DTYPE[dtype]
+    assert_spmm_close(C.float().cpu().numpy(), C64, absprod, RTOL[dtype], "C=A*B")
+    # bit-reproducible (no floating-point atomics)
+    C2 = I.insum_spmm_groupcoo(A, Bd)
+    assert torch.equal(C, C2)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_spmm_groupcoo_accumulate_strides_and_f32_out(I, dtype):
+    M, K, N, g = 700, 900, 96, 4
+    row, col, val = synth.zipf_rows_coo(M, K, 1.2, 8.0, seed=2, dtype=dtype, values="normal")
+    keep = row % 4 != 1                       # empty rows must keep their old contents
+    row, col, val = row[keep], col[keep], val[keep]
+    fmt = oracle.coo_to_groupcoo(M, K, row, col, synth.storage_array(val, dtype), g)
+    B = synth.round_to_dtype(np.random.default_rng(0).standard_normal((K, N)), dtype)
+    C0 = synth.round_to_dtype(np.random.default_rng(1).standard_normal((M, N)), dtype)
+    C64, absprod = _oracle_group_spmm(M, K, N, fmt, dtype, B, C0.astype(np.float64))
+    A = _gpu_group_format(I, M, K, fmt, dtype)
+    # B and C are column slices of wider buffers: ldb, ldc > N
+    Bw = torch.zeros((K, N + 32), dtype=TORCH_DTYPE[dtype], device="cuda")
+    Bw[:, :N] = values_to_torch(B, dtype)
+    Cw = torch.full((M, N + 16), 7.0, dtype=TORCH_DTYPE[dtype], device="cuda")
+    Cw[:, :N] = values_to_torch(C0, dtype)
+    I.insum_spmm_groupcoo(A, Bw[:, :N], C_out=Cw[:, :N], accumulate=True)
+    assert_spmm_close(Cw[:, :N].float().cpu().numpy(), C64, absprod, RTOL[dtype], "C+=A*B")
+    assert torch.all(Cw[:, N:] == 7.0), "wrote outside the N columns"
+    # fp32 output for 16-bit inputs
+    C64b, absb = _oracle_group_spmm(M, K, N, fmt, dtype, B)
+    Cf = I.insum_spmm_groupcoo(A, Bw[:, :N], out_dtype=torch.float32)
+    assert Cf.dtype == torch.float32
+    assert_spmm_close(Cf.cpu().numpy(), C64b, absb, RTOL[dtype] if dtype != "f32" else 1e-5, "f32 out")
+
+
+def test_spmm_groupcoo_empty_format_and_errors(I):
+    A = I.GroupCOO(6, 5, 2, torch.zeros(0, dtype=torch.int32, device="cuda"),
+                   torch.zeros((0, 2), dtype=torch.int32, device="cuda"),
+                   torch.zeros((0, 2), device="cuda"))
+    B = torch.ones((5, 12), device="cuda")
+    C = torch.full((6, 12), 3.0, device="cuda")
+    I.insum_spmm_groupcoo(A, B, C_out=C)
+    assert not C.any()
+    A2 = I.GroupCOO(6, 5, 2, torch.zeros(1, dtype=torch.int32, device="cuda"),
+                    torch.zeros((1, 2), dtype=torch.int32, device="cuda"),
+                    torch.zeros((1, 2), dtype=torch.float16, device="cuda"))
+    with pytest.raises(I.InsumError) as ex:
+        I.insum_spmm_groupcoo(A2, B)            # fp16 A with fp32 B
+    assert ex.value.status == 5
+    with pytest.raises(I.InsumError) as ex:     # workspace too small
+        A3 = I.GroupCOO(6, 5, 2, A2.AM, A2.AK, torch.zeros((1, 2), device="cuda"))
+        I.insum_spmm_groupcoo(A3, B, workspace=torch.empty(8, dtype=torch.uint8, device="cuda"))
+    assert ex.value.status == 4
+
+
+# --------------------------------------------------------------------------- #
+# SpMM over BlockGroupCOO
+# --------------------------------------------------------------------------- #
+def _oracle_block_spmm(M, K, N, bM, bK, fmt, dtype, B, C0=None):
+    g, AM, AK, AV = fmt
+    av = to_f32(AV, dtype)
+    C64 = oracle.spmm_blockgroupcoo(M, K, N, bM, bK, AM, AK, av, B, C_init=C0)
+    absprod = oracle.spmm_blockgroupcoo(M, K, N, bM, bK, AM, AK, np.abs(av), np.abs(B),
+                                        C_init=None if C0 is None else np.abs(C0))
+    return C64, absprod
+
+
+def _gpu_block_format(I, M, K, bM, bK, fmt, dtype):
+    g, AM, AK, AV = fmt
+    return I.BlockGroupCOO(M, K, bM, bK, g, torch.from_numpy(AM).cuda(), torch.from_numpy(AK).cuda(),
+                           storage_to_torch(AV, dtype))
+
+
+SPMM_BLOCK_CASES = [
+    # M, K, N, bM, bK, g, dtype, density
+    (64, 64, 64, 32, 32, 1, "bf16", 1.0),
+    (256, 384, 256, 32, 32, 4, "bf16", 0.3),
+    (256, 384, 512, 32, 32, 4, "f16", 0.3),
+    (512, 512, 264, 64, 64, 4, "bf16", 0.4),      # ragged column tile
+    (512, 512, 1000, 64, 64, 2, "f16", 0.3),
+    (512, 1024, 128, 64, 32, 3, "bf16", 0.3),
+    (256, 512, 72, 32, 16, 4, "bf16", 0.5),
+    (256, 1024, 320, 32, 128, 2, "f16", 0.5),     # two k-chunks per block
+    (256, 768, 64, 64, 48, 4, "bf16", 0.5),       # bK = 48 -> 16-wide k-chunks
+    (2048, 2048, 512, 32, 32, 4, "bf16", 0.1),    # cfg4 shape, smaller
+    (2048, 2048, 1024, 64, 64, 4, "bf16", 0.05),  # cfg5 shape, smaller; empty block rows
+    (96, 160, 40, 8, 16, 3, "f32", 0.4),          # general kernel
+    (120, 90, 33, 4, 2, 2, "f16", 0.3),
+    (128, 128, 50, 16, 16, 2, "bf16", 0.5),
+    (256, 256, 36, 32, 32, 4, "bf16", 0.5),       # N % 8 != 0 -> general kernel
+]
+
+
+@pytest.mark.parametrize("M,K,N,bM,bK,g,dtype,density", SPMM_BLOCK_CASES)
+def test_spmm_blockgroupcoo_parity(I, M, K, N, bM, bK, g, dtype, density):
+    _say(f"[spmm blockgroupcoo] M={M} K={K} N={N} b={bM}x{bK} g={g} {dtype}")
+    row, col, val = synth.random_block_coo(M, K, bM, bK, seed=N + bK, dtype=dtype,
+                                           block_density=density, sigma=0.5)
+    fmt = oracle.coo_to_blockgroupcoo(M, K, row, col, synth.storage_array(val, dtype), bM, bK, g)
+    B = synth.round_to_dtype(np.random.default_rng(N).standard_normal((K, N)), dtype)
+    C64, absprod = _oracle_block_spmm(M, K, N, bM, bK, fmt, dtype, B)
+    A = _gpu_block_format(I, M, K, bM, bK, fmt, dtype)
+    Bd = values_to_torch(B, dtype)
+    C = I.insum_spmm_blockgroupcoo(A, Bd)
+    assert_spmm_close(C.float().cpu().numpy(), C64, absprod, RTOL[dtype], "C=A*B")
+    assert torch.equal(C, I.insum_spmm_blockgroupcoo(A, Bd))
+
+
+@pytest.mark.parametrize("bM,bK,N", [(32, 32, 256), (64, 64, 520), (8, 8, 40)])
+def test_spmm_blockgroupcoo_accumulate_and_f32_out(I, bM, bK, N):
+    M, K, g, dtype = 8 * bM, 12 * bK, 4, "bf16"
+    row, col, val = synth.random_block_coo(M, K, bM, bK, seed=1, dtype=dtype, block_density=0.3,
+                                           sigma=0.5)
+    keep = (row // bM) != 2                      # an empty block row keeps its old contents
+    row, col, val = row[keep], col[keep], val[keep]
+    fmt = oracle.coo_to_blockgroupcoo(M, K, row, col, synth.storage_array(val, dtype), bM, bK, g)
+    B = synth.round_to_dtype(np.random.default_rng(0).standard_normal((K, N)), dtype)
+    C0 = synth.round_to_dtype(np.random.default_rng(1).standard_normal((M, N)), dtype)
+    C64, absprod = _oracle_block_spmm(M, K, N, bM, bK, fmt, dtype, B, C0.astype(np.float64))
+    A = _gpu_block_format(I, M, K, bM, bK, fmt, dtype)
+    Bw = torch.zeros((K, N + 64), dtype=torch.bfloat16, device="cuda")
+    Bw[:, :N] = values_to_torch(B, dtype)
+    Cw = torch.full((M, N + 8), 7.0, dtype=torch.bfloat16, device="cuda")
+    Cw[:, :N] = values_to_torch(C0, dtype)
+    I.insum_spmm_blockgroupcoo(A, Bw[:, :N], C_out=Cw[:, :N], accumulate=True)
+    assert_spmm_close(Cw[:, :N].float().cpu().numpy(), C64, absprod, RTOL[dtype], "C+=A*B")
+    assert torch.all(Cw[:, N:] == 7.0)
+    C64b, absb = _oracle_block_spmm(M, K, N, bM, bK, fmt, dtype, B)
+    Cf = I.insum_spmm_blockgroupcoo(A, Bw[:, :N], out_dtype=torch.float32)
+    assert_spmm_close(Cf.cpu().numpy(), C64b, absb, RTOL[dtype], "f32 out")

@@ -1,0 +1,66 @@
+"""CPU-side checks of the shared library: it loads, exports every function the public
+header declares, and its host-only entry points agree with the oracle."""
+from __future__ import annotations
+
+import ctypes
+import os
+import re
+
+import numpy as np
+
+import oracle
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _lib():
+    import paper_2510_17505_amd as I
+    return I, ctypes.CDLL(I.library_path())
+
+
+def test_every_declared_symbol_is_exported():
+    I, lib = _lib()
+    header = open(os.path.join(ROOT, "include", "insum.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = sorted(set(re.findall(r"\b(insum_[a-z0-9_]+)\s*\(", header)))
+    assert {"insum_coo_to_groupcoo", "insum_coo_to_blockgroupcoo", "insum_spmm_groupcoo",
+            "insum_spmm_blockgroupcoo"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in insum.h but not exported"
+
+
+def test_host_entry_points():
+    I, _ = _lib()
+    assert I.insum_version() >= 100
+    assert I.insum_status_string(0) == "ok"
+    assert "duplicate" in I.insum_status_string(3)
+    rng = np.random.default_rng(0)
+    for _ in range(500):
+        n = int(rng.integers(1, 2**31 - 1))
+        S = int(rng.integers(0, 2**31 - 1))
+        assert I.insum_default_group_size(S, n) == oracle.default_group_size(S, n)
+    for S, n in [(0, 5), (5, 0), (1999, 1000), (2000, 1000), (7999, 1000), (8000, 1000),
+                 (1677722, 4096), (1638, 128)]:
+        assert I.insum_default_group_size(S, n) == oracle.default_group_size(S, n)
+    occ = rng.integers(0, 50, 300)
+    for g in (1, 2, 3, 4, 7, 16, 64):
+        assert I.insum_indirect_access_cost(occ.tolist(), g) == oracle.indirect_access_cost(occ, g)
+    assert I.insum_indirect_access_cost([3, 1, 1, 2], 2) == 15
+
+
+def test_argument_validation_without_a_gpu():
+    """Calls that are rejected before any device work can be exercised on the CPU."""
+    I, lib = _lib()
+    lib.insum_spmm_groupcoo.restype = ctypes.c_int
+    i64, i32, p = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p
+    lib.insum_spmm_groupcoo.argtypes = [i64, i64, i64, i64, i32, p, p, p, ctypes.c_int, p, i64,
+                                        ctypes.c_int, p, i64, ctypes.c_int, ctypes.c_int, p,
+                                        ctypes.c_size_t, p]
+    call = lib.insum_spmm_groupcoo
+    assert call(4, 4, 4, 1, 0, 0, 0, 0, 0, 0, 4, 0, 0, 4, 0, 0, 0, 0, 0) == 1     # g <= 0
+    assert call(4, 4, 4, 1, 2, 0, 0, 0, 1, 0, 4, 0, 0, 4, 0, 0, 0, 0, 0) == 5     # dtype mix
+    assert call(4, 4, 4, 1, 2, 0, 0, 0, 0, 0, 2, 0, 0, 4, 0, 0, 0, 0, 0) == 1     # ldb < N
+    assert call(4, 4, 4, 1, 2, 0, 0, 0, 0, 0, 4, 0, 0, 4, 0, 0, 0, 0, 0) == 1     # null C
+    assert call(0, 4, 4, 0, 2, 0, 0, 0, 0, 0, 4, 0, 0, 4, 0, 0, 0, 0, 0) == 0     # empty problem
+    assert I.insum_spmm_groupcoo_workspace_bytes(1 << 20, 128, 4_600_000, 4) > 0
+    assert I.insum_spmm_blockgroupcoo_workspace_bytes(8192, 512, 1760, 4, 32, 32) == 0
