@@ -1,0 +1,64 @@
+"""The five benchmark workloads at full size, in the launch configuration bench.py times
+(default group size, library conversion feeding library SpMM): conversion bit-exact and
+SpMM within tolerance of the fp64 oracle on every output element."""
+from __future__ import annotations
+
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from gpu_util import RTOL, assert_format_equal, coo_to_device, values_to_torch
+from helpers import assert_spmm_close, to_f32
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+EXPECTED_G = {"cfg1": 2, "cfg2": 16, "cfg3": 4, "cfg4": 4, "cfg5": 4}
+
+
+@pytest.mark.parametrize("name", synth.CONFIG_NAMES)
+def test_full_config(name):
+    import paper_2510_17505_amd as I
+    t0 = time.time()
+    print(f"[full config] {name}: generating", flush=True)
+    cfg = synth.make_config(name)
+    M, K, N, dt = cfg["M"], cfg["K"], cfg["N"], cfg["a_dtype"]
+    st = synth.storage_array(cfg["val"], dt)
+    dev = coo_to_device(cfg["row"], cfg["col"], cfg["val"], dt)
+    print(f"[full config] {name}: nnz={cfg['row'].size}, converting on the GPU ({time.time()-t0:.1f}s)", flush=True)
+    if cfg["kind"] == "group":
+        A = I.insum_coo_to_groupcoo(M, K, *dev, g=0)
+        print(f"[full config] {name}: oracle conversion ({time.time()-t0:.1f}s)", flush=True)
+        want = oracle.coo_to_groupcoo(M, K, cfg["row"], cfg["col"], st, None)
+    else:
+        A = I.insum_coo_to_blockgroupcoo(M, K, *dev, cfg["bM"], cfg["bK"], g=0)
+        print(f"[full config] {name}: oracle conversion ({time.time()-t0:.1f}s)", flush=True)
+        want = oracle.coo_to_blockgroupcoo(M, K, cfg["row"], cfg["col"], st, cfg["bM"], cfg["bK"], None)
+    assert A.g == EXPECTED_G[name]
+    assert_format_equal(A.g, A.AM, A.AK, A.AV, want)
+    del dev
+    g, AM, AK, AV = want
+    av = to_f32(AV, dt)
+    print(f"[full config] {name}: G={AM.size}, SpMM on the GPU ({time.time()-t0:.1f}s)", flush=True)
+    Bd = values_to_torch(cfg["B"], cfg["b_dtype"])
+    if cfg["kind"] == "group":
+        C = I.insum_spmm_groupcoo(A, Bd)
+    else:
+        C = I.insum_spmm_blockgroupcoo(A, Bd)
+    torch.cuda.synchronize()
+    got = C.float().cpu().numpy()
+    del C, Bd, A
+    print(f"[full config] {name}: oracle SpMM ({time.time()-t0:.1f}s)", flush=True)
+    if cfg["kind"] == "group":
+        C64 = oracle.spmm_groupcoo(M, K, N, AM, AK, av, cfg["B"])
+        absprod = oracle.spmm_groupcoo(M, K, N, AM, AK, np.abs(av), np.abs(cfg["B"]))
+    else:
+        C64 = oracle.spmm_blockgroupcoo(M, K, N, cfg["bM"], cfg["bK"], AM, AK, av, cfg["B"])
+        absprod = oracle.spmm_blockgroupcoo(M, K, N, cfg["bM"], cfg["bK"], AM, AK, np.abs(av),
+                                            np.abs(cfg["B"]))
+    print(f"[full config] {name}: comparing ({time.time()-t0:.1f}s)", flush=True)
+    assert_spmm_close(got, C64, absprod, RTOL[dt], name)
+    print(f"[full config] {name}: ok ({time.time()-t0:.1f}s)", flush=True)
