@@ -168,6 +168,9 @@ def main():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--no-extra", action="store_true", help="skip the other configs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                    help="only run a plain elementwise copy of MIB mebibytes (read MIB, write MIB) "
+                         "--steps times: the known-size kernel that scales the HBM counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -178,6 +181,14 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.calibrate_copy:
+        n = args.calibrate_copy * (1 << 20) // 4
+        x = torch.ones(n, dtype=torch.float32, device="cuda")
+        y = torch.empty_like(x)
+        ms = _time_launches(torch, lambda: torch.mul(x, 1.0, out=y), args.steps, args.warmup)
+        print(json.dumps({"calibrate_copy_mib": args.calibrate_copy, "ms_per_step": ms,
+                          "copy_gbs": 2.0 * n * 4 / ms / 1e6}))
+        return
     import paper_2510_17505_amd as I
 
     res, (cfg, A, B, C) = run_workload(torch, I, args.workload, args.steps, args.warmup)
