@@ -10,6 +10,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libinsum.so")
+PEAKS_LIB = os.path.join(PKG, "libinsum_peaks.so")   # achievable-peak microbenchmarks (bench.py --peaks)
 
 SOURCES = ["misc.cpp", "convert.hip", "spmm_groupcoo.hip", "spmm_blockgroupcoo.hip"]
 
@@ -42,8 +43,13 @@ def _compile(src: str) -> str:
 def build(verbose: bool = False) -> str:
     """Compile every source (always) and link the shared library."""
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=4) as ex:
-        objs = list(ex.map(_compile, SOURCES))
+    with ThreadPoolExecutor(max_workers=5) as ex:
+        objs = list(ex.map(_compile, SOURCES + ["peaks.hip"]))
+    peaks_obj = objs.pop()
+    res = subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", PEAKS_LIB, peaks_obj],
+                         capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"link failed:\n{res.stderr[-4000:]}")
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:

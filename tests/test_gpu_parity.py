@@ -172,6 +172,9 @@ SPMM_GROUP_CASES = [
     (300, 100000, 64, 90000, 32, "f16", "hub"),
     (5000, 5000, 32, 4000, 4, "f32", "uniform"),       # mostly empty rows
     (64, 64, 24, 4096, 64, "bf16", "uniform"),         # dense matrix, g = row length
+    (64, 4096, 128, 60000, 128, "f32", "uniform"),     # g larger than a sub-wave batch
+    (2, 3, 5, 6, 1, "f32", "uniform"),                 # tiny dense
+    (100000, 50, 16, 3000, 4, "f32", "uniform"),       # long runs of empty rows to zero-fill
 ]
 
 
@@ -273,6 +276,11 @@ SPMM_BLOCK_CASES = [
     (120, 90, 33, 4, 2, 2, "f16", 0.3),
     (128, 128, 50, 16, 16, 2, "bf16", 0.5),
     (256, 256, 36, 32, 32, 4, "bf16", 0.5),       # N % 8 != 0 -> general kernel
+    (128, 4800, 256, 32, 32, 1, "bf16", 0.9),     # ~135 blocks per block row: several 64-slot batches
+    (128, 4800, 264, 32, 32, 7, "f16", 0.9),      # g not a power of two, ragged tile
+    (128, 4800, 256, 32, 32, 128, "bf16", 0.9),   # g > 64: whole batches of padding
+    (192, 6400, 512, 64, 64, 3, "bf16", 0.8),     # 80 blocks x 2 k-chunks per block row
+    (64, 64, 8, 64, 64, 4, "bf16", 1.0),          # one block, N = 8 (a single 16-byte chunk)
 ]
 
 
