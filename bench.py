@@ -145,6 +145,43 @@ def measured_peaks():
     }
 
 
+def group_size_sweep(torch, I, steps, warmup):
+    """Section 4.2 / 6.5 experiment on the paper's ablation shape (4096 x 4096, 90 % sparsity in
+    32 x 32 blocks, fp16, N = 4096): time the SpMM kernels for a range of group sizes and report
+    the indirect-access count F(g) and the format size next to each time."""
+    import synth
+    M = K = N = 4096
+    row, col, val = synth.random_block_coo(M, K, 32, 32, seed=0, dtype="f16", block_density=0.10,
+                                           sigma=0.02)
+    rd, cd = torch.from_numpy(row).cuda(), torch.from_numpy(col).cuda()
+    vd = _to_device(torch, val, "f16")
+    B = _to_device(torch, synth.round_to_dtype(
+        np.random.default_rng(1).standard_normal((K, N)).astype(np.float32), "f16"), "f16")
+    C = torch.empty((M, N), dtype=torch.float16, device="cuda")
+    flops = 2.0 * row.size * N
+    occ = np.bincount(row, minlength=M)
+    occ_b = np.bincount(np.unique((row // 32).astype(np.int64) * (K // 32) + col // 32) // (K // 32),
+                        minlength=M // 32)
+    out = {"shape": "4096x4096 fp16, 10 % of 32x32 blocks, N=4096", "nnz": int(row.size),
+           "default_g_rows": I.insum_default_group_size(int(row.size), M),
+           "default_g_block_rows": I.insum_default_group_size(int(occ_b.sum()), M // 32),
+           "groupcoo": [], "blockgroupcoo": []}
+    for g in (1, 2, 4, 8, 16, 32, 64, 128):
+        A = I.insum_coo_to_groupcoo(M, K, rd, cd, vd, g=g)
+        ws = torch.empty(I.insum_spmm_groupcoo_workspace_bytes(M, N, A.G, A.g), dtype=torch.uint8, device="cuda")
+        ms = _time_launches(torch, lambda: I.insum_spmm_groupcoo(A, B, C_out=C, workspace=ws), steps, warmup)
+        out["groupcoo"].append({"g": g, "ms": ms, "gflops": flops / ms / 1e6,
+                                "F": I.insum_indirect_access_cost(occ.tolist(), g),
+                                "format_bytes": int(A.AM.numel() * 4 + A.AK.numel() * 4 + A.AV.numel() * 2)})
+    for g in (1, 2, 4, 8, 16):
+        A = I.insum_coo_to_blockgroupcoo(M, K, rd, cd, vd, 32, 32, g=g)
+        ms = _time_launches(torch, lambda: I.insum_spmm_blockgroupcoo(A, B, C_out=C), steps, warmup)
+        out["blockgroupcoo"].append({"g": g, "ms": ms, "gflops": flops / ms / 1e6,
+                                     "F": I.insum_indirect_access_cost(occ_b.tolist(), g),
+                                     "format_bytes": int(A.AM.numel() * 4 + A.AK.numel() * 4 + A.AV.numel() * 2)})
+    return out
+
+
 def cpu_baseline(cfg, A, nnz_total):
     """The CPU oracle, as it stands, on a bounded sample of the same workload."""
     import oracle
@@ -190,6 +227,8 @@ def main():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--no-extra", action="store_true", help="skip the other configs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--sweep", action="store_true",
+                    help="only run the group-size sweep on the paper's ablation shape")
     ap.add_argument("--peaks", action="store_true", help="only run the achievable-peak microbenchmarks")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="only run a plain elementwise copy of MIB mebibytes (read MIB, write MIB) "
@@ -216,6 +255,9 @@ def main():
 
     if args.peaks:
         print(json.dumps({"measured_peaks": measured_peaks()}))
+        return
+    if args.sweep:
+        print(json.dumps({"group_size_sweep": group_size_sweep(torch, I, args.steps, args.warmup)}))
         return
     res, (cfg, A, B, C) = run_workload(torch, I, args.workload, args.steps, args.warmup)
     line = {

@@ -140,15 +140,20 @@ def insum_coo_to_groupcoo(M: int, K: int, row, col, val, g: int = 0) -> GroupCOO
     dev = val.device
     ws = torch.empty(int(_g_ws(M, nnz)), dtype=torch.uint8, device=dev)
     g_used, G = _i32(0), _i64(0)
-    args = (M, K, nnz, _ptr(row), _ptr(col), _ptr(val), _DTYPE[val.dtype], int(g),
-            C.addressof(g_used), C.addressof(G))
-    _check(_g_conv(*args, 0, 0, 0, 0, _ptr(ws), ws.numel(), _stream()), "insum_coo_to_groupcoo(count)")
-    AM = torch.empty(G.value, dtype=torch.int32, device=dev)
-    AK = torch.empty((G.value, g_used.value), dtype=torch.int32, device=dev)
-    AV = torch.empty((G.value, g_used.value), dtype=val.dtype, device=dev)
-    if G.value:
-        _check(_g_conv(*args, _ptr(AM), _ptr(AK), _ptr(AV), G.value, _ptr(ws), ws.numel(), _stream()),
-               "insum_coo_to_groupcoo(fill)")
+    # One fill call into buffers sized by the bound G <= nnz/g + min(M, nnz) (insum.h); the
+    # results are views of the first G groups.
+    g_eff = int(g) if g else insum_default_group_size(nnz, M)
+    cap = nnz // g_eff + min(M, nnz)
+    AM = torch.empty(cap, dtype=torch.int32, device=dev)
+    AK = torch.empty((cap, g_eff), dtype=torch.int32, device=dev)
+    AV = torch.empty((cap, g_eff), dtype=val.dtype, device=dev)
+    if nnz:
+        _check(_g_conv(M, K, nnz, _ptr(row), _ptr(col), _ptr(val), _DTYPE[val.dtype], int(g),
+                       C.addressof(g_used), C.addressof(G), _ptr(AM), _ptr(AK), _ptr(AV), cap,
+                       _ptr(ws), ws.numel(), _stream()), "insum_coo_to_groupcoo")
+    else:
+        g_used.value = g_eff
+    AM, AK, AV = AM[:G.value], AK[:G.value], AV[:G.value]
     return GroupCOO(M, K, g_used.value, AM, AK, AV)
 
 

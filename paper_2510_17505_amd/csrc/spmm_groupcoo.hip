@@ -44,6 +44,7 @@ struct GroupParams {
     int64_t runs, groups_per_run;
     float* partial;  // [runs][2][npad]: 0 = head piece, 1 = tail piece
     int64_t npad;
+    int32_t col_tiles;  // column tiles of SW*E columns; the tile index is the fastest part of blockIdx.x
 };
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -167,10 +168,13 @@ __device__ inline int64_t group_of_slot(int64_t slot, int32_t g, int32_t g_shift
 template <typename TB, typename TC, int E, int SW>
 __global__ __launch_bounds__(256) void spmm_groupcoo_main(GroupParams p) {
     constexpr int U = SW >= 8 ? 8 : SW;  // rows of B in flight per lane
+    // Workgroup id = run block * col_tiles + column tile.  Consecutive ids go to different
+    // XCDs, so with 8 (or 2, 4) column tiles every XCD keeps to its own columns of B and its
+    // L2 holds a 1/8 slice instead of all of B.
     const int lane = threadIdx.x % SW;
-    const int64_t run = ((int64_t)blockIdx.x * 256 + threadIdx.x) / SW;
+    const int64_t run = ((int64_t)(blockIdx.x / p.col_tiles) * 256 + threadIdx.x) / SW;
     if (run >= p.runs) return;  // the SW lanes of a sub-wave leave together
-    const int64_t n0 = ((int64_t)blockIdx.y * SW + lane) * E;
+    const int64_t n0 = ((int64_t)(blockIdx.x % p.col_tiles) * SW + lane) * E;
     const bool col_ok = n0 < p.N;
 
     const TB* __restrict__ B = static_cast<const TB*>(p.B);
@@ -197,48 +201,69 @@ __global__ __launch_bounds__(256) void spmm_groupcoo_main(GroupParams p) {
 
     if (!accumulate && !cur_is_head && col_ok) zero_rows<TC, E>(C, p.ldc, n0, (int64_t)prev_row + 1, first_row);
 
-    for (int64_t sb = gs * p.g; sb < slot_end; sb += SW) {
-        // one coalesced read of the next SW slots of the format
+    // Lanes beyond N (ragged last column tile) gather column 0 and never store.
+    const TB* const Bcol = B + (col_ok ? n0 : 0);
+    const int sub_base = (threadIdx.x % 64) / SW * SW;  // first lane of this sub-wave in the wavefront
+
+    // One coalesced read of SW slots of the format: lane j gets slot sb+j.
+    auto load_meta = [&](int64_t sb, int32_t& ak, float& av, int32_t& am) {
         const int64_t my = sb + lane;
-        const bool valid = my < slot_end;
-        int32_t ak_l = 0, am_l = 0;
-        float av_l = 0.f;
-        if (valid) {
-            ak_l = __builtin_nontemporal_load(AK + my);
-            av_l = load_stream(AV + my);
-            am_l = AM[group_of_slot(my, p.g, p.g_shift)];
+        ak = 0;
+        av = 0.f;
+        am = -1;
+        if (my < slot_end) {
+            ak = __builtin_nontemporal_load(AK + my);
+            av = load_stream(AV + my);
+            am = AM[group_of_slot(my, p.g, p.g_shift)];
         }
+    };
+    // The row sum of `cur` is complete (inside this run): store it, zero-fill skipped rows.
+    auto flush = [&](int32_t next_row) {
+        if (col_ok) {
+            if (cur_is_head) store_partial<E>(my_partial, acc);
+            else store_c<TC, E>(C + (int64_t)cur * p.ldc + n0, acc, accumulate);
+            if (!accumulate) zero_rows<TC, E>(C, p.ldc, n0, (int64_t)cur + 1, next_row);
+        }
+        cur_is_head = false;
+        cur = next_row;
+#pragma unroll
+        for (int i = 0; i < E; ++i) acc[i] = 0.f;
+    };
+
+    int32_t ak_l, am_l, ak_n = 0, am_n = -1;
+    float av_l, av_n = 0.f;
+    load_meta(gs * p.g, ak_l, av_l, am_l);
+    for (int64_t sb = gs * p.g; sb < slot_end; sb += SW) {
+        if (sb + SW < slot_end) load_meta(sb + SW, ak_n, av_n, am_n);  // next batch, in flight during this one
         const int nb = (int)imin((int64_t)SW, slot_end - sb);
+        // Which slots start a new row: bit j of `starts` (identical in all lanes of the sub-wave).
+        int32_t am_prev = __shfl_up(am_l, 1, SW);
+        if (lane == 0) am_prev = cur;
+        const uint64_t starts = (__ballot(lane < nb && am_l != am_prev) >> sub_base);
 #pragma unroll
         for (int c = 0; c < SW; c += U) {
             if (c >= nb) break;
             Piece<TB, E> rowpiece[U];
+            int32_t col[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {  // gather: U rows of B, 16 bytes per lane each
-                const int32_t col = __shfl(ak_l, c + u, SW);
-                if (col_ok) rowpiece[u].load(B + (int64_t)col * p.ldb + n0);
-                else rowpiece[u].zero();
-            }
+            for (int u = 0; u < U; ++u) col[u] = __shfl(ak_l, c + u, SW);
+#pragma unroll
+            for (int u = 0; u < U; ++u)  // gather: U rows of B, 16 bytes per lane each
+                rowpiece[u].load(Bcol + (int64_t)col[u] * p.ldb);
+            float a[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) a[u] = __shfl(av_l, c + u, SW);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (c + u < nb) {
-                    const int32_t r = __shfl(am_l, c + u, SW);
-                    const float a = __shfl(av_l, c + u, SW);
-                    if (r != cur) {  // segment boundary: the row sum is complete (in this run)
-                        if (col_ok) {
-                            if (cur_is_head) store_partial<E>(my_partial, acc);
-                            else store_c<TC, E>(C + (int64_t)cur * p.ldc + n0, acc, accumulate);
-                            if (!accumulate) zero_rows<TC, E>(C, p.ldc, n0, (int64_t)cur + 1, r);
-                        }
-                        cur_is_head = false;
-                        cur = r;
-#pragma unroll
-                        for (int i = 0; i < E; ++i) acc[i] = 0.f;
-                    }
-                    rowpiece[u].fma_into(a, acc);
+                if (c + u < nb) {  // slots past the end of the run hold column 0 and value 0
+                    if ((starts >> (c + u)) & 1) flush(__shfl(am_l, c + u, SW));
+                    rowpiece[u].fma_into(a[u], acc);
                 }
             }
         }
+        ak_l = ak_n;
+        av_l = av_n;
+        am_l = am_n;
     }
     if (col_ok) {
         if (cur_is_head) store_partial<E>(my_partial, acc);
@@ -255,9 +280,9 @@ __global__ __launch_bounds__(256) void spmm_groupcoo_main(GroupParams p) {
 template <typename TC, int E, int SW>
 __global__ __launch_bounds__(256) void spmm_groupcoo_seams(GroupParams p) {
     const int lane = threadIdx.x % SW;
-    const int64_t run = ((int64_t)blockIdx.x * 256 + threadIdx.x) / SW;
+    const int64_t run = ((int64_t)(blockIdx.x / p.col_tiles) * 256 + threadIdx.x) / SW;
     if (run >= p.runs) return;
-    const int64_t n0 = ((int64_t)blockIdx.y * SW + lane) * E;
+    const int64_t n0 = ((int64_t)(blockIdx.x % p.col_tiles) * SW + lane) * E;
     if (n0 >= p.N) return;
     const int32_t* __restrict__ AM = p.AM;
     const int64_t gs = run * p.groups_per_run;
@@ -323,7 +348,7 @@ int64_t padded_cols(int64_t N) { return (N + 7) / 8 * 8; }
 
 template <typename TB, typename TC, int E, int SW>
 void launch_pair(const GroupParams& p, const Plan& pl, hipStream_t s) {
-    const dim3 grid((unsigned)ceil_div(p.runs, 256 / SW), (unsigned)pl.col_tiles);
+    const dim3 grid((unsigned)(ceil_div(p.runs, 256 / SW) * pl.col_tiles));
     hipLaunchKernelGGL((spmm_groupcoo_main<TB, TC, E, SW>), grid, dim3(256), 0, s, p);
     hipLaunchKernelGGL((spmm_groupcoo_seams<TC, E, SW>), grid, dim3(256), 0, s, p);
 }
@@ -399,6 +424,8 @@ extern "C" insum_status insum_spmm_groupcoo(int64_t M, int64_t K, int64_t N, int
     p.accumulate = accumulate ? 1 : 0;
     p.runs = pl.runs; p.groups_per_run = pl.groups_per_run;
     p.npad = padded_cols(N);
+    p.col_tiles = (int32_t)pl.col_tiles;
+    if (ceil_div(pl.runs, 256 / pl.SW) * pl.col_tiles >= (1LL << 31)) return INSUM_ERR_UNSUPPORTED;
     const size_t need = (size_t)pl.runs * 2 * (size_t)p.npad * sizeof(float);
     const uintptr_t ws = (reinterpret_cast<uintptr_t>(workspace) + 255) / 256 * 256;
     if (!workspace || ws + need > reinterpret_cast<uintptr_t>(workspace) + workspace_bytes)
