@@ -64,14 +64,17 @@ def prepare(torch, I, name):
     col = torch.from_numpy(cfg["col"]).cuda()
     val = _to_device(torch, cfg["val"], cfg["a_dtype"])
     B = _to_device(torch, cfg["B"], cfg["b_dtype"])
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    if cfg["kind"] == "group":
-        A = I.insum_coo_to_groupcoo(cfg["M"], cfg["K"], row, col, val, g=0)
-    else:
-        A = I.insum_coo_to_blockgroupcoo(cfg["M"], cfg["K"], row, col, val, cfg["bM"], cfg["bK"], g=0)
-    torch.cuda.synchronize()
-    conv_ms = (time.perf_counter() - t0) * 1e3
+    conv_ms = None
+    for _ in range(2):      # the second call sees a warm allocator: that one is reported
+        A = None
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        if cfg["kind"] == "group":
+            A = I.insum_coo_to_groupcoo(cfg["M"], cfg["K"], row, col, val, g=0)
+        else:
+            A = I.insum_coo_to_blockgroupcoo(cfg["M"], cfg["K"], row, col, val, cfg["bM"], cfg["bK"], g=0)
+        torch.cuda.synchronize()
+        conv_ms = (time.perf_counter() - t0) * 1e3
     nnz = int(cfg["row"].shape[0])
     del row, col, val
     return cfg, A, B, nnz, conv_ms
@@ -101,12 +104,16 @@ def run_workload(torch, I, name, steps, warmup):
         "M": M, "K": cfg["K"], "N": N, "nnz": nnz, "g": A.g, "groups": A.G, "stored_units": int(stored),
         "dtype": cfg["a_dtype"], "ms_per_step": ms, "gflops": flops / ms / 1e6,
         "model_bytes": int(model_bytes), "model_gbs": model_bytes / ms / 1e6,
-        "conversion_ms_incl_alloc": conv_ms,
+        "conversion_ms": conv_ms,
     }
     if cfg["kind"] == "group":
         res["roofline"] = {"bound": "hbm", "achieved": res["model_gbs"], "peak": HBM_PEAK_GBS,
                            "unit": "GB/s", "frac": res["model_gbs"] / HBM_PEAK_GBS,
                            "traffic": _traffic(name)}
+        if cfg["K"] * N * sB <= (32 << 20):
+            res["roofline"]["note"] = ("B fits the 8 x 4 MiB L2: the gathers are served by the caches, "
+                                       "so algorithmic GB/s can exceed the HBM peak and HBM is not what "
+                                       "bounds this workload")
     else:
         tf = flops / ms / 1e9
         res["roofline"] = {"bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS,
@@ -270,7 +277,7 @@ def main():
                    "format": res["format"], "g": res["g"], "groups": res["groups"]},
         "roofline": res["roofline"],
         "model_bytes_per_launch": res["model_bytes"],
-        "conversion_ms_incl_alloc": res["conversion_ms_incl_alloc"],
+        "conversion_ms": res["conversion_ms"],
     }
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(cfg, A, res["nnz"])
@@ -285,7 +292,7 @@ def main():
             del keep
             torch.cuda.empty_cache()
             others[name] = {k: r[k] for k in ("format", "dtype", "nnz", "N", "g", "ms_per_step", "gflops",
-                                              "model_gbs", "roofline", "conversion_ms_incl_alloc")}
+                                              "model_gbs", "roofline", "conversion_ms")}
         line["other_workloads"] = others
         line["measured_peaks"] = measured_peaks()
     print(json.dumps(line))

@@ -311,34 +311,52 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_block_mfma(BlockParams p, Til
     for (int ks = 0; ks < KS; ++ks) a_lane[ks] = (lane % 32) * 64 + (((2 * ks + lane / 32) ^ a_swz) * 16);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void_ptr)lds;
 
+    // Operand fragments of k-step ks are requested while the MFMAs of k-step ks-1 run
+    // (two register sets); lgkmcnt counts LDS reads in order, so waiting until only the
+    // reads of the next k-step are outstanding means the current ones have arrived.
+    constexpr int READS = MI + 2 * NI;  // LDS reads per k-step and wavefront
     auto compute = [&](int buf) {
         const uint32_t sb = lds0 + buf * STAGE_BYTES;
         const uint32_t b_addr = sb + tr_base;
+        i16x8 a[2][MI];
+        i16x4 blo[2][NI], bhi[2][NI];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const uint32_t a_addr = sb + B_INSTR * 1024 + a_lane[ks];
-            i16x8 a[MI];
-            i16x4 blo[NI], bhi[NI];
+        for (int ks = 0; ks <= KS; ++ks) {
+            if (ks < KS) {
+                const int set = ks % 2;
+                const uint32_t a_addr = sb + B_INSTR * 1024 + a_lane[ks];
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-                asm volatile("ds_read_b128 %0, %1 offset:%2"
-                             : "=v"(a[mi]) : "v"(a_addr), "n"(mi * 2048) : "memory");
+                for (int mi = 0; mi < MI; ++mi) {
+                    if (mi == 0) asm volatile("ds_read_b128 %0, %1" : "=v"(a[set][0]) : "v"(a_addr) : "memory");
+                    else asm volatile("ds_read_b128 %0, %1 offset:2048" : "=v"(a[set][1]) : "v"(a_addr) : "memory");
+                }
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni) {
-                asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2"
-                             : "=v"(blo[ni]) : "v"(b_addr), "n"(((4 * ks + 0) * (NT / 32) + ni) * 256) : "memory");
-                asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2"
-                             : "=v"(bhi[ni]) : "v"(b_addr), "n"(((4 * ks + 1) * (NT / 32) + ni) * 256) : "memory");
+                for (int ni = 0; ni < NI; ++ni) {
+                    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2"
+                                 : "=v"(blo[set][ni]) : "v"(b_addr), "n"(((4 * ks + 0) * (NT / 32) + ni) * 256) : "memory");
+                    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2"
+                                 : "=v"(bhi[set][ni]) : "v"(b_addr), "n"(((4 * ks + 1) * (NT / 32) + ni) * 256) : "memory");
+                }
             }
-            if constexpr (MI == 2)
-                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[0]), "+v"(a[1]), "+v"(blo[0]), "+v"(bhi[0]), "+v"(blo[1]), "+v"(bhi[1]) :: "memory");
-            else
-                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[0]), "+v"(blo[0]), "+v"(bhi[0]), "+v"(blo[1]), "+v"(bhi[1]) :: "memory");
+            if (ks > 0) {
+                const int set = (ks - 1) % 2;
+                if (ks < KS) {  // the reads of k-step ks stay outstanding
+                    if constexpr (MI == 2)
+                        asm volatile("s_waitcnt lgkmcnt(%6)" : "+v"(a[set][0]), "+v"(a[set][1]), "+v"(blo[set][0]), "+v"(bhi[set][0]), "+v"(blo[set][1]), "+v"(bhi[set][1]) : "n"(READS) : "memory");
+                    else
+                        asm volatile("s_waitcnt lgkmcnt(%5)" : "+v"(a[set][0]), "+v"(blo[set][0]), "+v"(bhi[set][0]), "+v"(blo[set][1]), "+v"(bhi[set][1]) : "n"(READS) : "memory");
+                } else {
+                    if constexpr (MI == 2)
+                        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[set][0]), "+v"(a[set][1]), "+v"(blo[set][0]), "+v"(bhi[set][0]), "+v"(blo[set][1]), "+v"(bhi[set][1]) :: "memory");
+                    else
+                        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[set][0]), "+v"(blo[set][0]), "+v"(bhi[set][0]), "+v"(blo[set][1]), "+v"(bhi[set][1]) :: "memory");
+                }
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni) {
-                const i16x8 b = __builtin_shufflevector(blo[ni], bhi[ni], 0, 1, 2, 3, 4, 5, 6, 7);
+                for (int ni = 0; ni < NI; ++ni) {
+                    const i16x8 b = __builtin_shufflevector(blo[set][ni], bhi[set][ni], 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
-                for (int mi = 0; mi < MI; ++mi) acc[mi][ni] = mfma32<T>(b, a[mi], acc[mi][ni]);
+                    for (int mi = 0; mi < MI; ++mi) acc[mi][ni] = mfma32<T>(b, a[set][mi], acc[mi][ni]);
+                }
             }
         }
     };
