@@ -321,3 +321,65 @@ def test_spmm_blockgroupcoo_accumulate_and_f32_out(I, bM, bK, N):
     C64b, absb = _oracle_block_spmm(M, K, N, bM, bK, fmt, dtype, B)
     Cf = I.insum_spmm_blockgroupcoo(A, Bw[:, :N], out_dtype=torch.float32)
     assert_spmm_close(Cf.cpu().numpy(), C64b, absb, RTOL[dtype], "f32 out")
+
+
+# --------------------------------------------------------------------------- #
+# robustness
+# --------------------------------------------------------------------------- #
+def test_spmm_groupcoo_hub_rows_large(I):
+    """Rank-size-like degree distribution: a few rows hold most of the nonzeros, so single
+    rows span hundreds of work ranges and the seam pass does most of the reduction."""
+    M, K, N, g = 4096, 1 << 18, 128, 4
+    rng = np.random.default_rng(7)
+    occ = np.minimum((K // 2) // np.arange(1, M + 1), K // 2).astype(np.int64)   # 131072, 65536, ...
+    occ[64:] = rng.integers(0, 4, M - 64)
+    row = np.repeat(np.arange(M, dtype=np.int32), occ)
+    col = np.concatenate([rng.choice(K, size=int(k), replace=False) for k in occ]).astype(np.int32)
+    val = rng.standard_normal(row.size).astype(np.float32)
+    perm = rng.permutation(row.size)
+    row, col, val = row[perm], col[perm], val[perm]
+    _say(f"[spmm groupcoo hub] nnz={row.size}")
+    fmt = oracle.coo_to_groupcoo(M, K, row, col, val, g)
+    A = I.insum_coo_to_groupcoo(M, K, *coo_to_device(row, col, val, "f32"), g=g)
+    assert_format_equal(A.g, A.AM, A.AK, A.AV, fmt)
+    B = np.random.default_rng(1).standard_normal((K, N)).astype(np.float32)
+    C64, absprod = _oracle_group_spmm(M, K, N, fmt, "f32", B)
+    C = I.insum_spmm_groupcoo(A, values_to_torch(B, "f32"))
+    assert_spmm_close(C.cpu().numpy(), C64, absprod, RTOL["f32"], "hub rows")
+
+
+def test_spmm_calls_can_be_captured_in_a_hip_graph(I):
+    """Neither SpMM call allocates, synchronises or clears memory with a memset node, so a
+    caller may capture it.  The graph is replayed several times with eager work in between and
+    every replay must reproduce the eager result bit for bit."""
+    M, K, N = 1024, 2048, 256
+    row, col, val = synth.zipf_rows_coo(M, K, 1.2, 12.0, seed=3, dtype="f16", values="normal")
+    A = I.insum_coo_to_groupcoo(M, K, *coo_to_device(row, col, val, "f16"), g=4)
+    rb, cb, vb = synth.random_block_coo(M, K, 32, 32, seed=4, dtype="f16", block_density=0.2, sigma=0.5)
+    Ab = I.insum_coo_to_blockgroupcoo(M, K, *coo_to_device(rb, cb, vb, "f16"), 32, 32, g=4)
+    Bd = values_to_torch(synth.round_to_dtype(np.random.default_rng(0).standard_normal((K, N)), "f16"), "f16")
+    ws = torch.empty(I.insum_spmm_groupcoo_workspace_bytes(M, N, A.G, A.g), dtype=torch.uint8, device="cuda")
+    C1 = torch.empty((M, N), dtype=torch.float16, device="cuda")
+    C2 = torch.empty((M, N), dtype=torch.float16, device="cuda")
+    ref1 = I.insum_spmm_groupcoo(A, Bd, workspace=ws).clone()
+    ref2 = I.insum_spmm_blockgroupcoo(Ab, Bd).clone()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            I.insum_spmm_groupcoo(A, Bd, C_out=C1, workspace=ws)
+            I.insum_spmm_blockgroupcoo(Ab, Bd, C_out=C2)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(4):
+        C1.fill_(float("nan"))
+        C2.fill_(float("nan"))
+        ws.random_(0, 255)                       # stale scratch contents must not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(C1, ref1), f"GroupCOO replay {rep} differs"
+        assert torch.equal(C2, ref2), f"BlockGroupCOO replay {rep} differs"
+        _ = I.insum_spmm_groupcoo(A, Bd, workspace=ws)   # eager work between replays
+        torch.cuda.synchronize()

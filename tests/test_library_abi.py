@@ -64,3 +64,35 @@ def test_argument_validation_without_a_gpu():
     assert call(0, 4, 4, 0, 2, 0, 0, 0, 0, 0, 4, 0, 0, 4, 0, 0, 0, 0, 0) == 0     # empty problem
     assert I.insum_spmm_groupcoo_workspace_bytes(1 << 20, 128, 4_600_000, 4) > 0
     assert I.insum_spmm_blockgroupcoo_workspace_bytes(8192, 512, 1760, 4, 32, 32) == 0
+
+
+def test_conversion_argument_validation_without_a_gpu():
+    """The conversions reject malformed calls before touching the device."""
+    I, lib = _lib()
+    i64, i32, p = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p
+    g_used, G = i32(0), i64(0)
+    conv = lib.insum_coo_to_groupcoo
+    conv.restype = ctypes.c_int
+    conv.argtypes = [i64, i64, i64, p, p, p, ctypes.c_int, i32, p, p, p, p, p, i64, p, ctypes.c_size_t, p]
+    gu, gg = ctypes.addressof(g_used), ctypes.addressof(G)
+    assert conv(4, 4, -1, 0, 0, 0, 0, 2, gu, gg, 0, 0, 0, 0, 0, 0, 0) == 1          # nnz < 0
+    assert conv(4, 4, 3, 0, 0, 0, 0, 2, gu, gg, 0, 0, 0, 0, 0, 0, 0) == 1           # null inputs
+    assert conv(4, 4, 0, 0, 0, 0, 7, 2, gu, gg, 0, 0, 0, 0, 0, 0, 0) == 1           # bad dtype
+    assert conv(4, 4, 0, 0, 0, 0, 0, 2, 0, gg, 0, 0, 0, 0, 0, 0, 0) == 1            # null out-param
+    assert conv(4, 4, 0, 0, 0, 0, 0, 0, gu, gg, 0, 0, 0, 0, 0, 0, 0) == 0           # empty matrix is fine
+    assert g_used.value == 1 and G.value == 0
+    assert conv(1 << 31, 4, 0, 0, 0, 0, 0, 2, gu, gg, 0, 0, 0, 0, 0, 0, 0) == 1     # M too large for int32
+    bconv = lib.insum_coo_to_blockgroupcoo
+    bconv.restype = ctypes.c_int
+    bconv.argtypes = [i64, i64, i64, p, p, p, ctypes.c_int, i32, i32, i32, p, p, p, p, p, i64, p,
+                      ctypes.c_size_t, p]
+    assert bconv(9, 8, 0, 0, 0, 0, 0, 2, 2, 1, gu, gg, 0, 0, 0, 0, 0, 0, 0) == 5    # M % bM != 0
+    assert bconv(8, 8, 0, 0, 0, 0, 0, 0, 2, 1, gu, gg, 0, 0, 0, 0, 0, 0, 0) == 1    # bM <= 0
+    assert bconv(8, 8, 0, 0, 0, 0, 0, 2, 2, 0, gu, gg, 0, 0, 0, 0, 0, 0, 0) == 0
+    sb = lib.insum_spmm_blockgroupcoo
+    sb.restype = ctypes.c_int
+    sb.argtypes = [i64, i64, i64, i64, i32, i32, i32, p, p, p, ctypes.c_int, p, i64, ctypes.c_int, p, i64,
+                   ctypes.c_int, ctypes.c_int, p, ctypes.c_size_t, p]
+    assert sb(8, 8, 4, 0, 1, 3, 2, 0, 0, 0, 2, 0, 4, 2, 0, 4, 2, 0, 0, 0, 0) == 5   # M % bM != 0
+    assert sb(8, 8, 4, 0, 1, 2, 2, 0, 0, 0, 2, 0, 4, 1, 0, 4, 2, 0, 0, 0, 0) == 5   # dtype mix
+    assert sb(8, 8, 4, 0, 1, 2, 2, 0, 0, 0, 2, 0, 4, 2, 0, 4, 2, 0, 0, 0, 0) == 1   # null C
