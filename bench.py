@@ -189,6 +189,38 @@ def group_size_sweep(torch, I, steps, warmup):
     return out
 
 
+def vendor_context(torch, I, steps, warmup):
+    """Context only (not part of the library): the vendor SpMM that PyTorch dispatches to
+    (rocSPARSE CSR) on cfg3 and cfg2, and the dense GEMM (hipBLASLt) on the sweep shape - the
+    MI355X analogues of the cuSPARSE and dense-matmul comparisons in Section 6.2 / 6.3."""
+    import synth
+    out = {}
+    for name in ("cfg3", "cfg2"):
+        cfg = synth.make_config(name)
+        M, K, N = cfg["M"], cfg["K"], cfg["N"]
+        dt = _torch_dtype(torch, cfg["a_dtype"])
+        order = np.lexsort((cfg["col"], cfg["row"]))
+        crow = np.concatenate([[0], np.cumsum(np.bincount(cfg["row"], minlength=M))]).astype(np.int64)
+        try:
+            A = torch.sparse_csr_tensor(torch.from_numpy(crow).cuda(),
+                                        torch.from_numpy(cfg["col"][order].astype(np.int64)).cuda(),
+                                        _to_device(torch, cfg["val"][order], cfg["a_dtype"]), size=(M, K))
+            B = _to_device(torch, cfg["B"], cfg["b_dtype"])
+            ms = _time_launches(torch, lambda: torch.sparse.mm(A, B), steps, warmup)
+            out[name] = {"library": "torch.sparse.mm on a CSR tensor (rocSPARSE)", "dtype": str(dt),
+                         "ms": ms, "gflops": 2.0 * cfg["row"].size * N / ms / 1e6}
+            del A, B
+        except Exception as e:      # context only: report and go on
+            out[name] = {"error": f"{type(e).__name__}: {e}"[:200]}
+        torch.cuda.empty_cache()
+    a = torch.randn((4096, 4096), dtype=torch.float16, device="cuda")
+    b = torch.randn((4096, 4096), dtype=torch.float16, device="cuda")
+    ms = _time_launches(torch, lambda: torch.matmul(a, b), steps, warmup)
+    out["dense_4096_f16"] = {"library": "torch.matmul (hipBLASLt)", "ms": ms,
+                             "tflops": 2.0 * 4096 ** 3 / ms / 1e9}
+    return out
+
+
 def cpu_baseline(cfg, A, nnz_total):
     """The CPU oracle, as it stands, on a bounded sample of the same workload."""
     import oracle
@@ -236,6 +268,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--sweep", action="store_true",
                     help="only run the group-size sweep on the paper's ablation shape")
+    ap.add_argument("--context", action="store_true",
+                    help="only time the vendor libraries PyTorch dispatches to (context, not product)")
     ap.add_argument("--peaks", action="store_true", help="only run the achievable-peak microbenchmarks")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="only run a plain elementwise copy of MIB mebibytes (read MIB, write MIB) "
@@ -262,6 +296,9 @@ def main():
 
     if args.peaks:
         print(json.dumps({"measured_peaks": measured_peaks()}))
+        return
+    if args.context:
+        print(json.dumps({"vendor_context": vendor_context(torch, I, args.steps, args.warmup)}))
         return
     if args.sweep:
         print(json.dumps({"group_size_sweep": group_size_sweep(torch, I, args.steps, args.warmup)}))
