@@ -1,0 +1,79 @@
+"""Seeded random-shape sweep: many small problems with awkward sizes (N not a multiple of
+the vector width, single rows, empty rows, g larger than any row, block rows without blocks)
+through conversion and SpMM, each compared with the oracle."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from gpu_util import RTOL, assert_format_equal, coo_to_device, values_to_torch
+from helpers import assert_spmm_close, to_f32
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_groupcoo_problem(seed):
+    import paper_2510_17505_amd as I
+    rng = np.random.default_rng(1000 + seed)
+    M = int(rng.integers(1, 400))
+    K = int(rng.integers(1, 400))
+    N = int(rng.choice([1, 2, 3, 4, 7, 8, 12, 16, 31, 32, 64, 100, 128, 129, 256, 260, 513]))
+    dtype = ["f32", "f16", "bf16"][seed % 3]
+    g = int(rng.choice([0, 1, 2, 3, 4, 5, 8, 16, 33, 64, 200]))
+    density = float(rng.choice([0.0, 0.002, 0.02, 0.2, 0.9]))
+    nnz = int(density * M * K)
+    print(f"[random groupcoo] seed={seed} M={M} K={K} N={N} g={g} {dtype} nnz={nnz}", flush=True)
+    row, col, val = synth.random_coo(M, K, nnz, seed, dtype)
+    if nnz > 4 and seed % 4 == 0:            # duplicates
+        row = np.concatenate([row, row[:3]]); col = np.concatenate([col, col[:3]])
+        val = np.concatenate([val, val[:3]])
+    st = synth.storage_array(val, dtype)
+    want = oracle.coo_to_groupcoo(M, K, row, col, st, g or None)
+    A = I.insum_coo_to_groupcoo(M, K, *coo_to_device(row, col, val, dtype), g=g)
+    assert_format_equal(A.g, A.AM, A.AK, A.AV, want)
+    B = synth.round_to_dtype(rng.standard_normal((K, N)), dtype)
+    gg, AM, AK, AV = want
+    av = to_f32(AV, dtype)
+    C0 = synth.round_to_dtype(rng.standard_normal((M, N)), dtype) if seed % 2 else None
+    C64 = oracle.spmm_groupcoo(M, K, N, AM, AK, av, B, C_init=None if C0 is None else C0.astype(np.float64))
+    absprod = oracle.spmm_groupcoo(M, K, N, AM, AK, np.abs(av), np.abs(B),
+                                   C_init=None if C0 is None else np.abs(C0).astype(np.float64))
+    Bd = values_to_torch(B, dtype)
+    if C0 is None:
+        C = I.insum_spmm_groupcoo(A, Bd)
+    else:
+        C = values_to_torch(C0, dtype)
+        I.insum_spmm_groupcoo(A, Bd, C_out=C, accumulate=True)
+    assert_spmm_close(C.float().cpu().numpy(), C64, absprod, RTOL[dtype], f"seed {seed}")
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_random_blockgroupcoo_problem(seed):
+    import paper_2510_17505_amd as I
+    rng = np.random.default_rng(2000 + seed)
+    bM = int(rng.choice([1, 2, 8, 16, 32, 32, 64, 64]))
+    bK = int(rng.choice([1, 4, 16, 32, 32, 64, 64, 96, 128]))
+    M = bM * int(rng.integers(1, 9))
+    K = bK * int(rng.integers(1, 12))
+    N = int(rng.choice([1, 5, 8, 16, 24, 64, 128, 136, 256, 264, 512, 520]))
+    dtype = ["bf16", "f16", "f32"][seed % 3]
+    g = int(rng.choice([0, 1, 2, 3, 4, 8, 70]))
+    density = float(rng.choice([0.0, 0.1, 0.5, 1.0]))
+    print(f"[random blockgroupcoo] seed={seed} M={M} K={K} N={N} b={bM}x{bK} g={g} {dtype} d={density}", flush=True)
+    row, col, val = synth.random_block_coo(M, K, bM, bK, seed, dtype, block_density=density, sigma=0.5,
+                                           fill=1.0 if seed % 2 else 0.6)
+    st = synth.storage_array(val, dtype)
+    want = oracle.coo_to_blockgroupcoo(M, K, row, col, st, bM, bK, g or None)
+    A = I.insum_coo_to_blockgroupcoo(M, K, *coo_to_device(row, col, val, dtype), bM, bK, g=g)
+    assert_format_equal(A.g, A.AM, A.AK, A.AV, want)
+    B = synth.round_to_dtype(rng.standard_normal((K, N)), dtype)
+    gg, AM, AK, AV = want
+    av = to_f32(AV, dtype)
+    C64 = oracle.spmm_blockgroupcoo(M, K, N, bM, bK, AM, AK, av, B)
+    absprod = oracle.spmm_blockgroupcoo(M, K, N, bM, bK, AM, AK, np.abs(av), np.abs(B))
+    C = I.insum_spmm_blockgroupcoo(A, values_to_torch(B, dtype))
+    assert_spmm_close(C.float().cpu().numpy(), C64, absprod, RTOL[dtype], f"seed {seed}")
