@@ -2,15 +2,18 @@
 //
 // The paper fixes the result (fixed-length groups along rows / block rows, the row stored
 // once per group, padding inside a row's last group) but not an algorithm.  Here:
-//   1. one pass validates coordinates, counts entries per row and forms a 64-bit sort key
+//   1. one pass validates coordinates and forms a 64-bit sort key
 //      (GroupCOO: row*K + col; blocks: ((block row, block col), position inside block));
-//   2. a stable radix sort of (key, input position) gives the canonical order
-//      (row, col, input position);
-//   3. prefix sums of ceil(occ/g) give each row's first group; G goes back to the host;
-//   4. one pass scatters every sorted entry to group = first_group[row] + rank/g,
-//      slot = rank % g, and the last entry of a row also writes that group's padding.
-// Values are moved as raw bits; there is no floating-point arithmetic, so the output is a
-// pure function of the input.
+//   2. a stable radix sort of (key, value bits) gives the canonical order (row, col, input
+//      position): equal keys keep their input order, so the position never has to be stored,
+//      and the values arrive already permuted (no random gather afterwards);
+//   3. row (block-row) boundaries are read off the sorted keys, prefix sums of ceil(occ/g)
+//      give each row's first group, and G goes back to the host;
+//   4. one streaming pass writes every sorted entry to group = first_group[row] + rank/g,
+//      slot = rank % g; the last entry of a row also writes that group's padding.
+// Count mode (no output buffers) only needs per-row counts and uses an atomic histogram
+// instead of the sort.  Values are moved as raw bits; there is no floating-point arithmetic,
+// so the output is a pure function of the input.
 //
 // The device-wide sort and prefix sums are rocPRIM's (library primitives); everything
 // specific to the formats is in the kernels of this file.
@@ -36,6 +39,15 @@ int bits_for(uint64_t max_value) {  // number of low bits that can be set in [0,
     return std::max(b, 1);
 }
 
+// Division of sort keys by a per-launch constant (K, or bM*bK): a shift when it is a power
+// of two, a 64-bit division otherwise.
+struct Divisor {
+    uint64_t d;
+    int32_t shift;  // log2(d) or -1
+    explicit Divisor(uint64_t v) : d(v), shift((v & (v - 1)) == 0 ? __builtin_ctzll(v) : -1) {}
+    __device__ uint64_t div(uint64_t x) const { return shift >= 0 ? (x >> shift) : (x / d); }
+};
+
 // ---- workspace carving -------------------------------------------------------------------
 struct Carver {
     uintptr_t cur, end;
@@ -58,12 +70,16 @@ struct Carver {
     }
 };
 
-size_t sort_temp_bytes(int64_t nnz) {
+template <typename V>
+size_t sort_temp_bytes_v(int64_t nnz) {
     size_t bytes = 0;
     uint64_t* k = nullptr;
-    uint32_t* v = nullptr;
+    V* v = nullptr;
     (void)rocprim::radix_sort_pairs(nullptr, bytes, k, k, v, v, (size_t)std::max<int64_t>(nnz, 1), 0, 64);
     return bytes;
+}
+size_t sort_temp_bytes(int64_t nnz) {
+    return std::max(sort_temp_bytes_v<uint32_t>(nnz), sort_temp_bytes_v<uint16_t>(nnz));
 }
 
 size_t scan_temp_bytes(int64_t n) {
@@ -81,55 +97,82 @@ struct Flags {  // device-side status words, copied to the host with the counts
     int32_t total_b;  // Blocks: G
 };
 
-// ---- kernels: GroupCOO ---------------------------------------------------------------------
+// ---- kernels shared by both formats -----------------------------------------------------------
 __global__ void k_zero_i32(int32_t* p, int64_t n) {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i < n) p[i] = 0;
 }
 
+// start[r] = index of the first sorted entry whose row (key / per_row) is >= r, for r in
+// [0, nrows]; start[nrows] = nnz.  Thread i owns the rows in (row(i-1), row(i)].
+__global__ void k_row_bounds(int64_t nnz, int64_t nrows, Divisor per_row,
+                             const uint64_t* __restrict__ key, int32_t* __restrict__ start) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i > nnz) return;
+    const int64_t cur = i < nnz ? (int64_t)per_row.div(key[i]) : nrows;
+    const int64_t prev = i > 0 ? (int64_t)per_row.div(key[i - 1]) : -1;
+    for (int64_t r = prev + 1; r <= cur; ++r) start[r] = (int32_t)i;
+}
+
+// gpr[i] = ceil((start[i+1] - start[i]) / g) for i < n, gpr[n] = 0 (so that an exclusive
+// scan over n+1 elements ends with the total)
+__global__ void k_groups_from_bounds(int64_t n, const int32_t* __restrict__ start, int32_t g,
+                                     int32_t* __restrict__ gpr) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i > n) return;
+    gpr[i] = i < n ? (start[i + 1] - start[i] + g - 1) / g : 0;
+}
+
+// the same from per-row counts; in place
+__global__ void k_groups_from_counts(int64_t n, int32_t* occ, int32_t g) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i > n) return;
+    occ[i] = i < n ? (occ[i] + g - 1) / g : 0;
+}
+
+__global__ void k_store_total(const int32_t* src, int32_t* dst) { *dst = *src; }
+
+template <typename V>
+__global__ void k_fill_zero(V* p, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < n) p[i] = (V)0;
+}
+
+// ---- kernels: GroupCOO ---------------------------------------------------------------------
+template <bool HISTOGRAM>
 __global__ void k_group_keys(int64_t M, int64_t K, int64_t nnz, const int32_t* __restrict__ row,
                              const int32_t* __restrict__ col, uint64_t* __restrict__ key,
-                             uint32_t* __restrict__ pos, int32_t* __restrict__ occ, Flags* flags) {
+                             int32_t* __restrict__ occ, Flags* flags) {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= nnz) return;
     const int32_t r = row[i], c = col[i];
-    if (r < 0 || r >= M || c < 0 || c >= K) {
-        flags->out_of_range = 1;
-        key[i] = 0;
-        pos[i] = (uint32_t)i;
-        return;
+    const bool ok = r >= 0 && r < M && c >= 0 && c < K;
+    if (!ok) flags->out_of_range = 1;
+    if constexpr (HISTOGRAM) {
+        if (ok) atomicAdd(&occ[r], 1);
+    } else {
+        key[i] = ok ? (uint64_t)r * (uint64_t)K + (uint64_t)c : 0;
     }
-    key[i] = (uint64_t)r * (uint64_t)K + (uint64_t)c;
-    pos[i] = (uint32_t)i;
-    atomicAdd(&occ[r], 1);
-}
-
-// gpr[i] = ceil(occ[i] / g) for i < n, gpr[n] = 0 (so that an exclusive scan over n+1
-// elements ends with the total)
-__global__ void k_groups_per_row(int64_t n, const int32_t* occ, int32_t g, int32_t* gpr) {
-    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i > n) return;
-    gpr[i] = i < n ? (occ[i] + g - 1) / g : 0;
 }
 
 template <typename V>
-__global__ void k_group_fill(int64_t K, int64_t nnz, int32_t g, const uint64_t* __restrict__ key,
-                             const uint32_t* __restrict__ pos, const V* __restrict__ val,
-                             const int32_t* __restrict__ row_start,
+__global__ void k_group_fill(Divisor per_row, int64_t nnz, int32_t g, const uint64_t* __restrict__ key,
+                             const V* __restrict__ val, const int32_t* __restrict__ row_start,
                              const int32_t* __restrict__ grp_start, int32_t* __restrict__ AM,
                              int32_t* __restrict__ AK, V* __restrict__ AV) {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= nnz) return;
     const uint64_t k = key[i];
-    const int64_t r = (int64_t)(k / (uint64_t)K);
-    const int32_t c = (int32_t)(k - (uint64_t)r * (uint64_t)K);
-    const int32_t rank = (int32_t)(i - row_start[r]);
-    const int32_t occ = row_start[r + 1] - row_start[r];
+    const int64_t r = (int64_t)per_row.div(k);
+    const int32_t c = (int32_t)(k - (uint64_t)r * per_row.d);
+    const int32_t first = row_start[r];
+    const int32_t rank = (int32_t)(i - first);
+    const int32_t occ = row_start[r + 1] - first;
     const int64_t grp = (int64_t)grp_start[r] + rank / g;
     const int32_t slot = rank % g;
     const int64_t dst = grp * g + slot;
     AK[dst] = c;
-    AV[dst] = val[pos[i]];
+    AV[dst] = val[i];
     if (slot == 0) AM[grp] = (int32_t)r;
     if (rank == occ - 1) {  // last entry of its row: pad the rest of the group
         for (int32_t q = slot + 1; q < g; ++q) {
@@ -142,11 +185,10 @@ __global__ void k_group_fill(int64_t K, int64_t nnz, int32_t g, const uint64_t* 
 // ---- kernels: BlockGroupCOO ----------------------------------------------------------------
 __global__ void k_block_keys(int64_t M, int64_t K, int64_t nnz, int32_t bM, int32_t bK,
                              const int32_t* __restrict__ row, const int32_t* __restrict__ col,
-                             uint64_t* __restrict__ key, uint32_t* __restrict__ pos, Flags* flags) {
+                             uint64_t* __restrict__ key, Flags* flags) {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= nnz) return;
     const int32_t r = row[i], c = col[i];
-    pos[i] = (uint32_t)i;
     if (r < 0 || r >= M || c < 0 || c >= K) {
         flags->out_of_range = 1;
         key[i] = 0;
@@ -160,7 +202,7 @@ __global__ void k_block_keys(int64_t M, int64_t K, int64_t nnz, int32_t bM, int3
 // On sorted keys: head[i] = 1 when entry i is the first of its block; counts blocks per
 // block row; equal neighbouring keys are duplicate coordinates.  head has nnz+1 entries
 // (the last is 0) so its exclusive scan ends with the number of blocks.
-__global__ void k_block_heads(int64_t nnz, int64_t K, int32_t bM, int32_t bK,
+__global__ void k_block_heads(int64_t nnz, Divisor per_block, Divisor blocks_per_row,
                               const uint64_t* __restrict__ key, int32_t* __restrict__ head,
                               int32_t* __restrict__ occ, Flags* flags) {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
@@ -169,50 +211,41 @@ __global__ void k_block_heads(int64_t nnz, int64_t K, int32_t bM, int32_t bK,
         head[i] = 0;
         return;
     }
-    const uint64_t per_block = (uint64_t)bM * (uint64_t)bK;
-    const uint64_t blk = key[i] / per_block;
+    const uint64_t blk = per_block.div(key[i]);
     int32_t h = 1;
     if (i > 0) {
         const uint64_t prev = key[i - 1];
         if (prev == key[i]) flags->duplicate = 1;
-        h = (prev / per_block) != blk;
+        h = per_block.div(prev) != blk;
     }
     head[i] = h;
-    if (h) atomicAdd(&occ[blk / (uint64_t)(K / bK)], 1);
+    if (h) atomicAdd(&occ[blocks_per_row.div(blk)], 1);
 }
 
 template <typename V>
-__global__ void k_fill_zero(V* p, int64_t n) {
-    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i < n) p[i] = (V)0;
-}
-
-template <typename V>
-__global__ void k_block_fill(int64_t K, int64_t nnz, int32_t bM, int32_t bK, int32_t g,
-                             const uint64_t* __restrict__ key, const uint32_t* __restrict__ pos,
-                             const V* __restrict__ val, const int32_t* __restrict__ head,
-                             const int32_t* __restrict__ blk_ord,
+__global__ void k_block_fill(Divisor per_block, Divisor blocks_per_row, int64_t nnz, int32_t g,
+                             const uint64_t* __restrict__ key, const V* __restrict__ val,
+                             const int32_t* __restrict__ head, const int32_t* __restrict__ blk_ord,
                              const int32_t* __restrict__ brow_start,
                              const int32_t* __restrict__ grp_start, int32_t* __restrict__ AM,
                              int32_t* __restrict__ AK, V* __restrict__ AV) {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= nnz) return;
-    const uint64_t per_block = (uint64_t)bM * (uint64_t)bK;
-    const uint64_t nbc = (uint64_t)(K / bK);
     const uint64_t k = key[i];
-    const uint64_t blk = k / per_block;
-    const uint64_t inside = k - blk * per_block;  // bm * bK + bk
-    const int64_t br = (int64_t)(blk / nbc);
-    const int32_t bc = (int32_t)(blk - (uint64_t)br * nbc);
+    const uint64_t blk = per_block.div(k);
+    const uint64_t inside = k - blk * per_block.d;  // bm * bK + bk
+    const int64_t br = (int64_t)blocks_per_row.div(blk);
+    const int32_t bc = (int32_t)(blk - (uint64_t)br * blocks_per_row.d);
     // blk_ord is the exclusive scan of head: for a head entry it is the block's ordinal,
     // for the other entries of the block it is ordinal + 1.
-    const int32_t ord = blk_ord[i] - (head[i] ? 0 : 1);
+    const int32_t is_head = head[i];
+    const int32_t ord = blk_ord[i] - (is_head ? 0 : 1);
     const int32_t rank = ord - brow_start[br];
     const int32_t occ = brow_start[br + 1] - brow_start[br];
     const int64_t grp = (int64_t)grp_start[br] + rank / g;
     const int32_t slot = rank % g;
-    AV[((grp * g + slot) * (int64_t)per_block) + (int64_t)inside] = val[pos[i]];
-    if (head[i]) {
+    AV[((grp * g + slot) * (int64_t)per_block.d) + (int64_t)inside] = val[i];
+    if (is_head) {
         AK[grp * g + slot] = bc;
         if (slot == 0) AM[grp] = (int32_t)br;
         if (rank == occ - 1)
@@ -220,6 +253,7 @@ __global__ void k_block_fill(int64_t K, int64_t nnz, int32_t bM, int32_t bK, int
     }
 }
 
+// ---- host helpers ---------------------------------------------------------------------------
 template <typename T>
 insum_status scan_exclusive(void* temp, size_t temp_bytes, const T* in, T* out, int64_t n,
                             hipStream_t s) {
@@ -228,13 +262,23 @@ insum_status scan_exclusive(void* temp, size_t temp_bytes, const T* in, T* out, 
     return INSUM_OK;
 }
 
+template <typename V>
+insum_status sort_by_key(void* temp, size_t temp_bytes, const uint64_t* key_in, uint64_t* key_out,
+                         const void* val_in, void* val_out, int64_t nnz, int key_bits, hipStream_t s) {
+    size_t need = 0;
+    INSUM_HIP_TRY(rocprim::radix_sort_pairs(nullptr, need, key_in, key_out, static_cast<const V*>(val_in),
+                                            static_cast<V*>(val_out), (size_t)nnz, 0, key_bits, s));
+    if (need > temp_bytes) return INSUM_ERR_CAPACITY;
+    INSUM_HIP_TRY(rocprim::radix_sort_pairs(temp, need, key_in, key_out, static_cast<const V*>(val_in),
+                                            static_cast<V*>(val_out), (size_t)nnz, 0, key_bits, s));
+    return INSUM_OK;
+}
+
 insum_status read_flags(const Flags* d_flags, Flags* h, hipStream_t s) {
     INSUM_HIP_TRY(hipMemcpyAsync(h, d_flags, sizeof(Flags), hipMemcpyDeviceToHost, s));
     INSUM_HIP_TRY(hipStreamSynchronize(s));
     return INSUM_OK;
 }
-
-__global__ void k_store_total(const int32_t* src, int32_t* dst) { *dst = *src; }
 
 }  // namespace
 }  // namespace insum
@@ -245,11 +289,12 @@ using namespace insum;
 extern "C" size_t insum_coo_to_groupcoo_workspace_bytes(int64_t M, int64_t nnz) {
     M = std::max<int64_t>(M, 0);
     nnz = std::max<int64_t>(nnz, 0);
+    const size_t n1 = (size_t)std::max<int64_t>(nnz, 1);
     size_t b = 512;
     b += align_up(sizeof(Flags), 256);
-    b += 3 * align_up((size_t)(M + 1) * 4, 256);            // occ / groups-per-row, row_start, grp_start
-    b += 2 * align_up((size_t)std::max<int64_t>(nnz, 1) * 8, 256);  // keys in/out
-    b += 2 * align_up((size_t)std::max<int64_t>(nnz, 1) * 4, 256);  // positions in/out
+    b += 3 * align_up((size_t)(M + 1) * 4, 256);  // groups per row, row_start, grp_start
+    b += 2 * align_up(n1 * 8, 256);               // keys in/out
+    b += align_up(n1 * 4, 256);                   // sorted values
     b += align_up(std::max(sort_temp_bytes(nnz), scan_temp_bytes(M + 1)), 256);
     return b;
 }
@@ -275,26 +320,40 @@ extern "C" insum_status insum_coo_to_groupcoo(int64_t M, int64_t K, int64_t nnz,
 
     Carver ws(workspace, workspace_bytes);
     Flags* d_flags = ws.take<Flags>(1);
-    int32_t* occ = ws.take<int32_t>(M + 1);  // later reused for groups per row
+    int32_t* gpr = ws.take<int32_t>(M + 1);  // per-row counts, then groups per row
     int32_t* row_start = ws.take<int32_t>(M + 1);
     int32_t* grp_start = ws.take<int32_t>(M + 1);
     uint64_t* key_a = ws.take<uint64_t>(nnz);
     uint64_t* key_b = ws.take<uint64_t>(nnz);
-    uint32_t* pos_a = ws.take<uint32_t>(nnz);
-    uint32_t* pos_b = ws.take<uint32_t>(nnz);
+    uint32_t* val_b = ws.take<uint32_t>(nnz);
     const size_t temp_bytes = std::max(sort_temp_bytes(nnz), scan_temp_bytes(M + 1));
     void* temp = ws.take<char>(temp_bytes);
     if (!ws.ok) return INSUM_ERR_CAPACITY;
 
-    hipLaunchKernelGGL(k_zero_i32, dim3(blocks_for(M + 1)), dim3(kThreads), 0, s, occ, M + 1);
+    const Divisor per_row((uint64_t)K);
+    insum_status st;
     hipLaunchKernelGGL(k_zero_i32, dim3(1), dim3(kThreads), 0, s, reinterpret_cast<int32_t*>(d_flags),
                        (int64_t)(sizeof(Flags) / 4));
-    hipLaunchKernelGGL(k_group_keys, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, M, K, nnz, row, col,
-                       key_a, pos_a, occ, d_flags);
-    insum_status st = scan_exclusive(temp, temp_bytes, occ, row_start, M + 1, s);
-    if (st != INSUM_OK) return st;
-    hipLaunchKernelGGL(k_groups_per_row, dim3(blocks_for(M + 1)), dim3(kThreads), 0, s, M, occ, g, occ);
-    st = scan_exclusive(temp, temp_bytes, occ, grp_start, M + 1, s);
+    if (!fill) {  // count mode: atomic histogram of the rows, no sort
+        hipLaunchKernelGGL(k_zero_i32, dim3(blocks_for(M + 1)), dim3(kThreads), 0, s, gpr, M + 1);
+        hipLaunchKernelGGL(k_group_keys<true>, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, M, K, nnz, row,
+                           col, key_a, gpr, d_flags);
+        hipLaunchKernelGGL(k_groups_from_counts, dim3(blocks_for(M + 1)), dim3(kThreads), 0, s, M, gpr, g);
+    } else {
+        hipLaunchKernelGGL(k_group_keys<false>, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, M, K, nnz, row,
+                           col, key_a, gpr, d_flags);
+        INSUM_HIP_TRY(hipGetLastError());
+        const int key_bits = bits_for((uint64_t)M * (uint64_t)K - 1);
+        st = dtype_size(dt) == 4
+                 ? sort_by_key<uint32_t>(temp, temp_bytes, key_a, key_b, val, val_b, nnz, key_bits, s)
+                 : sort_by_key<uint16_t>(temp, temp_bytes, key_a, key_b, val, val_b, nnz, key_bits, s);
+        if (st != INSUM_OK) return st;
+        hipLaunchKernelGGL(k_row_bounds, dim3(blocks_for(nnz + 1)), dim3(kThreads), 0, s, nnz, M, per_row,
+                           key_b, row_start);
+        hipLaunchKernelGGL(k_groups_from_bounds, dim3(blocks_for(M + 1)), dim3(kThreads), 0, s, M, row_start,
+                           g, gpr);
+    }
+    st = scan_exclusive(temp, temp_bytes, gpr, grp_start, M + 1, s);
     if (st != INSUM_OK) return st;
     hipLaunchKernelGGL(k_store_total, dim3(1), dim3(1), 0, s, grp_start + M, &d_flags->total_a);
     INSUM_HIP_TRY(hipGetLastError());
@@ -307,20 +366,13 @@ extern "C" insum_status insum_coo_to_groupcoo(int64_t M, int64_t K, int64_t nnz,
     if (!fill) return INSUM_OK;
     if (capacity_groups < G) return INSUM_ERR_CAPACITY;
 
-    const int key_bits = bits_for((uint64_t)M * (uint64_t)K - 1);
-    size_t tb = 0;
-    INSUM_HIP_TRY(rocprim::radix_sort_pairs(nullptr, tb, key_a, key_b, pos_a, pos_b, (size_t)nnz, 0,
-                                            key_bits, s));
-    if (tb > temp_bytes) return INSUM_ERR_CAPACITY;
-    INSUM_HIP_TRY(rocprim::radix_sort_pairs(temp, tb, key_a, key_b, pos_a, pos_b, (size_t)nnz, 0,
-                                            key_bits, s));
     if (dtype_size(dt) == 4)
-        hipLaunchKernelGGL(k_group_fill<uint32_t>, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, K, nnz, g,
-                           key_b, pos_b, static_cast<const uint32_t*>(val), row_start, grp_start, AM, AK,
+        hipLaunchKernelGGL(k_group_fill<uint32_t>, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, per_row, nnz, g,
+                           key_b, reinterpret_cast<const uint32_t*>(val_b), row_start, grp_start, AM, AK,
                            static_cast<uint32_t*>(AV));
     else
-        hipLaunchKernelGGL(k_group_fill<uint16_t>, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, K, nnz, g,
-                           key_b, pos_b, static_cast<const uint16_t*>(val), row_start, grp_start, AM, AK,
+        hipLaunchKernelGGL(k_group_fill<uint16_t>, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, per_row, nnz, g,
+                           key_b, reinterpret_cast<const uint16_t*>(val_b), row_start, grp_start, AM, AK,
                            static_cast<uint16_t*>(AV));
     INSUM_HIP_TRY(hipGetLastError());
     INSUM_HIP_TRY(hipStreamSynchronize(s));
@@ -335,12 +387,13 @@ extern "C" size_t insum_coo_to_blockgroupcoo_workspace_bytes(int64_t M, int64_t 
     M = std::max<int64_t>(M, 0);
     nnz = std::max<int64_t>(nnz, 0);
     const int64_t nbr = bM > 0 ? M / bM : M;
+    const size_t n1 = (size_t)std::max<int64_t>(nnz, 1);
     size_t b = 512;
     b += align_up(sizeof(Flags), 256);
-    b += 3 * align_up((size_t)(nbr + 1) * 4, 256);           // occ, brow_start, grp_start
-    b += 2 * align_up((size_t)std::max<int64_t>(nnz, 1) * 8, 256);   // keys in/out
-    b += 2 * align_up((size_t)std::max<int64_t>(nnz, 1) * 4, 256);   // positions in/out
-    b += 2 * align_up((size_t)(nnz + 1) * 4, 256);           // head flags, block ordinals
+    b += 3 * align_up((size_t)(nbr + 1) * 4, 256);  // occ, brow_start, grp_start
+    b += 2 * align_up(n1 * 8, 256);                 // keys in/out
+    b += align_up(n1 * 4, 256);                     // sorted values
+    b += 2 * align_up((size_t)(nnz + 1) * 4, 256);  // head flags, block ordinals
     b += align_up(std::max({sort_temp_bytes(nnz), scan_temp_bytes(nnz + 1), scan_temp_bytes(nbr + 1)}), 256);
     return b;
 }
@@ -374,8 +427,7 @@ extern "C" insum_status insum_coo_to_blockgroupcoo(int64_t M, int64_t K, int64_t
     int32_t* grp_start = ws.take<int32_t>(nbr + 1);
     uint64_t* key_a = ws.take<uint64_t>(nnz);
     uint64_t* key_b = ws.take<uint64_t>(nnz);
-    uint32_t* pos_a = ws.take<uint32_t>(nnz);
-    uint32_t* pos_b = ws.take<uint32_t>(nnz);
+    uint32_t* val_b = ws.take<uint32_t>(nnz);
     int32_t* head = ws.take<int32_t>(nnz + 1);
     int32_t* blk_ord = ws.take<int32_t>(nnz + 1);
     const size_t temp_bytes =
@@ -383,22 +435,23 @@ extern "C" insum_status insum_coo_to_blockgroupcoo(int64_t M, int64_t K, int64_t
     void* temp = ws.take<char>(temp_bytes);
     if (!ws.ok) return INSUM_ERR_CAPACITY;
 
+    const Divisor per_block((uint64_t)bM * (uint64_t)bK);
+    const Divisor blocks_per_row((uint64_t)(K / bK));
     hipLaunchKernelGGL(k_zero_i32, dim3(blocks_for(nbr + 1)), dim3(kThreads), 0, s, occ, nbr + 1);
     hipLaunchKernelGGL(k_zero_i32, dim3(1), dim3(kThreads), 0, s, reinterpret_cast<int32_t*>(d_flags),
                        (int64_t)(sizeof(Flags) / 4));
     hipLaunchKernelGGL(k_block_keys, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, M, K, nnz, bM, bK, row,
-                       col, key_a, pos_a, d_flags);
+                       col, key_a, d_flags);
     INSUM_HIP_TRY(hipGetLastError());
     const int key_bits = bits_for((uint64_t)M * (uint64_t)K - 1);
-    size_t tb = 0;
-    INSUM_HIP_TRY(rocprim::radix_sort_pairs(nullptr, tb, key_a, key_b, pos_a, pos_b, (size_t)nnz, 0,
-                                            key_bits, s));
-    if (tb > temp_bytes) return INSUM_ERR_CAPACITY;
-    INSUM_HIP_TRY(rocprim::radix_sort_pairs(temp, tb, key_a, key_b, pos_a, pos_b, (size_t)nnz, 0,
-                                            key_bits, s));
-    hipLaunchKernelGGL(k_block_heads, dim3(blocks_for(nnz + 1)), dim3(kThreads), 0, s, nnz, K, bM, bK,
-                       key_b, head, occ, d_flags);
-    insum_status st = scan_exclusive(temp, temp_bytes, head, blk_ord, nnz + 1, s);
+    insum_status st =
+        dtype_size(dt) == 4
+            ? sort_by_key<uint32_t>(temp, temp_bytes, key_a, key_b, val, val_b, nnz, key_bits, s)
+            : sort_by_key<uint16_t>(temp, temp_bytes, key_a, key_b, val, val_b, nnz, key_bits, s);
+    if (st != INSUM_OK) return st;
+    hipLaunchKernelGGL(k_block_heads, dim3(blocks_for(nnz + 1)), dim3(kThreads), 0, s, nnz, per_block,
+                       blocks_per_row, key_b, head, occ, d_flags);
+    st = scan_exclusive(temp, temp_bytes, head, blk_ord, nnz + 1, s);
     if (st != INSUM_OK) return st;
     st = scan_exclusive(temp, temp_bytes, occ, brow_start, nbr + 1, s);
     if (st != INSUM_OK) return st;
@@ -413,7 +466,7 @@ extern "C" insum_status insum_coo_to_blockgroupcoo(int64_t M, int64_t K, int64_t
     if (g == 0) g = insum_default_group_size(num_blocks, nbr);
     *g_used = g;
 
-    hipLaunchKernelGGL(k_groups_per_row, dim3(blocks_for(nbr + 1)), dim3(kThreads), 0, s, nbr, occ, g, occ);
+    hipLaunchKernelGGL(k_groups_from_counts, dim3(blocks_for(nbr + 1)), dim3(kThreads), 0, s, nbr, occ, g);
     st = scan_exclusive(temp, temp_bytes, occ, grp_start, nbr + 1, s);
     if (st != INSUM_OK) return st;
     hipLaunchKernelGGL(k_store_total, dim3(1), dim3(1), 0, s, grp_start + nbr, &d_flags->total_b);
@@ -429,15 +482,15 @@ extern "C" insum_status insum_coo_to_blockgroupcoo(int64_t M, int64_t K, int64_t
     if (dtype_size(dt) == 4) {
         hipLaunchKernelGGL(k_fill_zero<uint32_t>, dim3(blocks_for(av_elems)), dim3(kThreads), 0, s,
                            static_cast<uint32_t*>(AV), av_elems);
-        hipLaunchKernelGGL(k_block_fill<uint32_t>, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, K, nnz, bM,
-                           bK, g, key_b, pos_b, static_cast<const uint32_t*>(val), head, blk_ord, brow_start,
-                           grp_start, AM, AK, static_cast<uint32_t*>(AV));
+        hipLaunchKernelGGL(k_block_fill<uint32_t>, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, per_block,
+                           blocks_per_row, nnz, g, key_b, reinterpret_cast<const uint32_t*>(val_b), head,
+                           blk_ord, brow_start, grp_start, AM, AK, static_cast<uint32_t*>(AV));
     } else {
         hipLaunchKernelGGL(k_fill_zero<uint16_t>, dim3(blocks_for(av_elems)), dim3(kThreads), 0, s,
                            static_cast<uint16_t*>(AV), av_elems);
-        hipLaunchKernelGGL(k_block_fill<uint16_t>, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, K, nnz, bM,
-                           bK, g, key_b, pos_b, static_cast<const uint16_t*>(val), head, blk_ord, brow_start,
-                           grp_start, AM, AK, static_cast<uint16_t*>(AV));
+        hipLaunchKernelGGL(k_block_fill<uint16_t>, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, per_block,
+                           blocks_per_row, nnz, g, key_b, reinterpret_cast<const uint16_t*>(val_b), head,
+                           blk_ord, brow_start, grp_start, AM, AK, static_cast<uint16_t*>(AV));
     }
     INSUM_HIP_TRY(hipGetLastError());
     INSUM_HIP_TRY(hipStreamSynchronize(s));
