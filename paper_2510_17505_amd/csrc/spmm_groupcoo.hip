@@ -11,9 +11,14 @@
 //     bytes, and no cross-lane reduction is needed for the products.
 //   * The run's slots are read with coalesced loads (lane j takes slot base+j: column,
 //     value and the row of its group) and handed to the other lanes with cross-lane
-//     shuffles, so the format is streamed exactly once.  B rows are fetched eight slots
-//     at a time before the first product is formed, which keeps 8 x 16 B per lane in
-//     flight.
+//     shuffles, so the format is streamed exactly once; the next batch of slots is
+//     requested before the current one is processed.  B rows are fetched eight slots at a
+//     time before the first product is formed (8 x 16 B per lane in flight), with the eight
+//     column shuffles issued back to back.  Which slots start a new row is one ballot per
+//     batch, so the inner loop tests a bit instead of shuffling and comparing row ids.
+//   * Wide B (more than 64 lanes x 16 bytes per row) is cut into column tiles; the tile
+//     index is the fastest-varying part of the workgroup id, so with 8 tiles each XCD keeps
+//     to one 1/8 column slice of B in its L2.
 //   * Scatter is a segment reduction: AM is non-decreasing, so the sub-wave keeps the row
 //     sum in registers while the row does not change and stores it once.  Rows between
 //     two stored rows have no groups; the sub-wave that sees the jump writes their zeros,
