@@ -175,10 +175,11 @@ size_t insum_spmm_blockgroupcoo_workspace_bytes(int64_t M, int64_t N, int64_t G,
  * C = A * B or C += A * B with A in BlockGroupCOO (layout as produced by
  * insum_coo_to_blockgroupcoo; M % bM == 0, K % bK == 0).
  *
- *   a_dt == b_dt in {F16, BF16}; c_dt == b_dt or F32.  Products are exact, sums are
- *   formed in fp32 on the matrix cores (MFMA) when bM is 32 or 64, bK is a multiple of 16
- *   up to 128, N and ldb are multiples of 8 and B, AV are 16-byte aligned; other shapes
- *   run on a slower general kernel with the same results up to summation order.
+ *   a_dt == b_dt in {F32, F16, BF16}; c_dt == b_dt or F32.  Products are exact, sums are
+ *   formed in fp32 on the matrix cores (MFMA) when bM is 32, 64 or 128, bK is a multiple
+ *   of 32, N and ldb are multiples of 8, ldc is a multiple of 8 (4 for fp32 C) and B, AV, C
+ *   are 16-byte aligned; other shapes, and a_dt == b_dt == F32, run on a slower general
+ *   kernel with the same results up to summation order.
  *   A padding block (one that repeats the previous block column of its group) is
  *   skipped; B is assumed finite.
  *

@@ -326,10 +326,9 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_block_mfma(BlockParams p, Til
                 const int set = ks % 2;
                 const uint32_t a_addr = sb + B_INSTR * 1024 + a_lane[ks];
 #pragma unroll
-                for (int mi = 0; mi < MI; ++mi) {
-                    if (mi == 0) asm volatile("ds_read_b128 %0, %1" : "=v"(a[set][0]) : "v"(a_addr) : "memory");
-                    else asm volatile("ds_read_b128 %0, %1 offset:2048" : "=v"(a[set][1]) : "v"(a_addr) : "memory");
-                }
+                for (int mi = 0; mi < MI; ++mi)
+                    asm volatile("ds_read_b128 %0, %1 offset:%2"
+                                 : "=v"(a[set][mi]) : "v"(a_addr), "n"(mi * 2048) : "memory");
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni) {
                     asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2"
@@ -340,17 +339,14 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_block_mfma(BlockParams p, Til
             }
             if (ks > 0) {
                 const int set = (ks - 1) % 2;
-                if (ks < KS) {  // the reads of k-step ks stay outstanding
-                    if constexpr (MI == 2)
-                        asm volatile("s_waitcnt lgkmcnt(%6)" : "+v"(a[set][0]), "+v"(a[set][1]), "+v"(blo[set][0]), "+v"(bhi[set][0]), "+v"(blo[set][1]), "+v"(bhi[set][1]) : "n"(READS) : "memory");
-                    else
-                        asm volatile("s_waitcnt lgkmcnt(%5)" : "+v"(a[set][0]), "+v"(blo[set][0]), "+v"(bhi[set][0]), "+v"(blo[set][1]), "+v"(bhi[set][1]) : "n"(READS) : "memory");
-                } else {
-                    if constexpr (MI == 2)
-                        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[set][0]), "+v"(a[set][1]), "+v"(blo[set][0]), "+v"(bhi[set][0]), "+v"(blo[set][1]), "+v"(bhi[set][1]) :: "memory");
-                    else
-                        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[set][0]), "+v"(blo[set][0]), "+v"(bhi[set][0]), "+v"(blo[set][1]), "+v"(bhi[set][1]) :: "memory");
-                }
+                // The reads of k-step ks (if any) stay outstanding.  The empty statements tie
+                // the fragment registers to the wait, so no MFMA that uses them moves above it.
+                if (ks < KS) asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(READS) : "memory");
+                else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi) asm volatile("" : "+v"(a[set][mi])::"memory");
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) asm volatile("" : "+v"(blo[set][ni]), "+v"(bhi[set][ni])::"memory");
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni) {
                     const i16x8 b = __builtin_shufflevector(blo[set][ni], bhi[set][ni], 0, 1, 2, 3, 4, 5, 6, 7);
@@ -519,6 +515,7 @@ void launch_typed(const BlockParams& p, bool mfma_ok, hipStream_t s) {
     if constexpr (sizeof(T) == 2) {
         if (mfma_ok && p.bM == 32) return launch_mfma_kc<T, TC, 32>(p, s);
         if (mfma_ok && p.bM == 64) return launch_mfma_kc<T, TC, 64>(p, s);
+        if (mfma_ok && p.bM == 128) return launch_mfma_kc<T, TC, 128>(p, s);
     }
     const dim3 grid((unsigned)(p.M / p.bM), (unsigned)ceil_div(p.N, 256));
     hipLaunchKernelGGL((spmm_block_general<T, TC>), grid, dim3(256), 0, s, p);

@@ -281,6 +281,8 @@ SPMM_BLOCK_CASES = [
     (128, 4800, 256, 32, 32, 128, "bf16", 0.9),   # g > 64: whole batches of padding
     (192, 6400, 512, 64, 64, 3, "bf16", 0.8),     # 80 blocks x 2 k-chunks per block row
     (64, 64, 8, 64, 64, 4, "bf16", 1.0),          # one block, N = 8 (a single 16-byte chunk)
+    (512, 1024, 512, 128, 64, 2, "bf16", 0.5),    # 128-row blocks (four MFMA row tiles)
+    (256, 768, 200, 128, 32, 3, "f16", 0.6),
 ]
 
 
