@@ -385,3 +385,19 @@ def test_spmm_calls_can_be_captured_in_a_hip_graph(I):
         assert torch.equal(C2, ref2), f"BlockGroupCOO replay {rep} differs"
         _ = I.insum_spmm_groupcoo(A, Bd, workspace=ws)   # eager work between replays
         torch.cuda.synchronize()
+
+
+def test_backward_spmm_is_the_same_path_on_the_transposed_coordinates(I):
+    """dB = A^T dC (the gradient of C = A B with respect to B): converting the COO entries with
+    rows and columns swapped gives A^T in GroupCOO, and the same SpMM call does the rest.
+    Checked against a dense fp64 product, with fp32 output for fp16 operands."""
+    M, K, N = 900, 1300, 96
+    row, col, val = synth.zipf_rows_coo(M, K, 1.2, 10.0, seed=11, dtype="f16", values="normal")
+    dC = synth.round_to_dtype(np.random.default_rng(5).standard_normal((M, N)), "f16")
+    At = I.insum_coo_to_groupcoo(K, M, *coo_to_device(col, row, val, "f16"), g=0)      # K x M
+    dB = I.insum_spmm_groupcoo(At, values_to_torch(dC, "f16"), out_dtype=torch.float32)
+    A = np.zeros((M, K))
+    np.add.at(A, (row, col), val.astype(np.float64))
+    ref = A.T @ dC.astype(np.float64)
+    absprod = np.abs(A).T @ np.abs(dC).astype(np.float64)
+    assert_spmm_close(dB.cpu().numpy(), ref, absprod, RTOL["f16"], "A^T dC")
