@@ -46,6 +46,14 @@ _lib.oracle_spmm_groupcoo.restype = None
 _lib.oracle_spmm_groupcoo.argtypes = [_i64] * 5 + [_p, _p, _p, _p, _i64, _p, _i64]
 _lib.oracle_spmm_blockgroupcoo.restype = None
 _lib.oracle_spmm_blockgroupcoo.argtypes = [_i64] * 7 + [_p, _p, _p, _p, _i64, _p, _i64]
+_lib.oracle_map_order.restype = C.c_int
+_lib.oracle_map_order.argtypes = [_i64, _i64, _i64, _i64, _p, _p, _p, _p]
+_lib.oracle_map_num_groups.restype = _i64
+_lib.oracle_map_num_groups.argtypes = [_i64, _i64, _p, _i64, _p]
+_lib.oracle_map_to_groupcoo.restype = C.c_int
+_lib.oracle_map_to_groupcoo.argtypes = [_i64, _i64, _i64, _i64, _p, _p, _p, _p, C.c_int, _i64, _p, _p, _p, _p]
+_lib.oracle_spconv_groupcoo.restype = None
+_lib.oracle_spconv_groupcoo.argtypes = [_i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _i64, _p, _p, _i64]
 _lib.oracle_num_threads.restype = C.c_int
 
 ERR_OUT_OF_RANGE = 2
@@ -193,6 +201,54 @@ def spmm_blockgroupcoo(M, K, N, bM, bK, AM, AK, AV, B, C_init=None) -> np.ndarra
     _lib.oracle_spmm_blockgroupcoo(M, K, N, G, g, bM, bK, _ptr(AM), _ptr(AK), _ptr(AV), _ptr(B),
                                    N, _ptr(Cd), N)
     return Cd
+
+
+def map_to_groupcoo(X, Y, Z, mx, my, mz, mv, g=None):
+    """Kernel map (COO of the 3-D tensor Map[x, y, z]) -> groups along z.
+    Returns (g, MAPZ[G], MAPX[G,g], MAPY[G,g], MAPV[G,g])."""
+    mx = np.ascontiguousarray(mx, dtype=np.int32)
+    my = np.ascontiguousarray(my, dtype=np.int32)
+    mz = np.ascontiguousarray(mz, dtype=np.int32)
+    mv = np.ascontiguousarray(mv)
+    nnz = mx.shape[0]
+    assert my.shape == (nnz,) and mz.shape == (nnz,) and mv.shape == (nnz,) and mv.dtype.itemsize in (2, 4)
+    if nnz and (mx.min() < 0 or mx.max() >= X or my.min() < 0 or my.max() >= Y or mz.min() < 0 or mz.max() >= Z):
+        raise OracleError(ERR_OUT_OF_RANGE)
+    if g is None or g == 0:
+        g = default_group_size(nnz, Z)
+    occ = np.empty(max(Z, 1), dtype=np.int64)
+    G = int(_lib.oracle_map_num_groups(Z, nnz, _ptr(mz), int(g), _ptr(occ)))
+    MAPZ = np.empty(G, dtype=np.int32)
+    MAPX = np.empty((G, g), dtype=np.int32)
+    MAPY = np.empty((G, g), dtype=np.int32)
+    MAPV = np.empty((G, g), dtype=mv.dtype)
+    rc = _lib.oracle_map_to_groupcoo(X, Y, Z, nnz, _ptr(mx), _ptr(my), _ptr(mz), _ptr(mv), mv.dtype.itemsize,
+                                     int(g), _ptr(MAPZ), _ptr(MAPX), _ptr(MAPY), _ptr(MAPV))
+    if rc:
+        raise OracleError(rc)
+    return int(g), MAPZ, MAPX, MAPY, MAPV
+
+
+def spconv_groupcoo(X, C_in, M_out, MAPZ, MAPX, MAPY, MAPV, In, W, Out_init=None) -> np.ndarray:
+    """fp64 result of Out[MAPX[p,q], m] += MAPV[p,q] * In[MAPY[p,q], c] * W[MAPZ[p], c, m]."""
+    MAPZ = np.ascontiguousarray(MAPZ, dtype=np.int32)
+    MAPX = np.ascontiguousarray(MAPX, dtype=np.int32)
+    MAPY = np.ascontiguousarray(MAPY, dtype=np.int32)
+    MAPV = _f32(MAPV)
+    In = _f32(In)
+    W = _f32(W)
+    G = MAPZ.shape[0]
+    g = MAPX.shape[1] if MAPX.ndim == 2 else 1
+    assert MAPX.size == G * g and MAPY.size == G * g and MAPV.size == G * g
+    assert In.ndim == 2 and In.shape[1] == C_in and W.ndim == 3 and W.shape[1:] == (C_in, M_out)
+    Out = np.zeros((X, M_out), dtype=np.float64) if Out_init is None else \
+        np.array(Out_init, dtype=np.float64, order="C")
+    if G:
+        assert MAPX.min() >= 0 and MAPX.max() < X and MAPY.min() >= 0 and MAPY.max() < In.shape[0]
+        assert MAPZ.min() >= 0 and MAPZ.max() < W.shape[0]
+    _lib.oracle_spconv_groupcoo(C_in, M_out, G, g, _ptr(MAPZ), _ptr(MAPX), _ptr(MAPY), _ptr(MAPV),
+                                _ptr(In), C_in, _ptr(W), _ptr(Out), M_out)
+    return Out
 
 
 def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:

@@ -12,7 +12,9 @@
  *   - the indirect-access count F(g), its relaxation and g* = sqrt(S/n):
  *     Section 4.2 "Choosing Group Size";
  *   - the SpMM loops: the "GroupCOO SpMM" listing of the ablation study (Section 6.5)
- *     and the BlockGroupCOO Einsum of Section 4.1.
+ *     and the BlockGroupCOO Einsum of Section 4.1;
+ *   - point-cloud sparse convolution as an indirect Einsum grouped by kernel offset:
+ *     Section 6.4 "Case Study: Point Cloud Sparse Convolution".
  *
  * Where the paper is silent the oracle takes these readings (listed again in the
  * design notes): entries are ordered by (row, column, input position); padding slots
@@ -312,6 +314,108 @@ void oracle_spmm_blockgroupcoo(int64_t M, int64_t K, int64_t N, int64_t G, int64
                         double* crow = C + ((int64_t)AM[p] * bM + bm) * ldc;
                         for (int64_t n = n0; n < n1; ++n) crow[n] += a * (double)brow[n];
                     }
+    }
+}
+
+/* ------------------------------------------------------------------------------------ */
+/* Point-cloud sparse convolution (Section 6.4)                                           */
+/*   Out[MAPX[p,q], m] += MAPV[p,q] * sum_c In[MAPY[p,q], c] * W[MAPZ[p], c, m]           */
+/* The map is a 3-D sparse tensor Map[x, y, z] stored as COO and grouped along z (the     */
+/* kernel offset): every group holds g (x, y, value) triples of one offset.               */
+/* ------------------------------------------------------------------------------------ */
+
+/* perm[i] = input position of the i-th entry in (z, x, position) order.  Returns 0, or 2
+ * when a coordinate is out of range. */
+int oracle_map_order(int64_t X, int64_t Y, int64_t Z, int64_t nnz, const int32_t* mx,
+                     const int32_t* my, const int32_t* mz, int64_t* perm) {
+    sort_item* it = (sort_item*)malloc(sizeof(sort_item) * (size_t)(nnz > 0 ? nnz : 1));
+    for (int64_t i = 0; i < nnz; ++i) {
+        if (mx[i] < 0 || mx[i] >= X || my[i] < 0 || my[i] >= Y || mz[i] < 0 || mz[i] >= Z) {
+            free(it);
+            return 2;
+        }
+        it[i].key_hi = mz[i];
+        it[i].key_lo = mx[i];
+        it[i].pos = i;
+    }
+    qsort(it, (size_t)nnz, sizeof(sort_item), cmp_item);
+    for (int64_t i = 0; i < nnz; ++i) perm[i] = it[i].pos;
+    free(it);
+    return 0;
+}
+
+/* occ[z] = entries with offset z; returns G = sum_z ceil(occ_z / g). */
+int64_t oracle_map_num_groups(int64_t Z, int64_t nnz, const int32_t* mz, int64_t g, int64_t* occ) {
+    for (int64_t z = 0; z < Z; ++z) occ[z] = 0;
+    for (int64_t e = 0; e < nnz; ++e) occ[mz[e]] += 1;
+    int64_t G = 0;
+    for (int64_t z = 0; z < Z; ++z) G += (occ[z] + g - 1) / g;
+    return G;
+}
+
+/* Fills MAPZ[G], MAPX[G*g], MAPY[G*g], MAPV[G*g].  Padding slots (tail of the last group
+ * of an offset) hold value +0 and repeat the x and y of the last real entry of the group. */
+int oracle_map_to_groupcoo(int64_t X, int64_t Y, int64_t Z, int64_t nnz, const int32_t* mx,
+                           const int32_t* my, const int32_t* mz, const void* mv, int elem_size,
+                           int64_t g, int32_t* MAPZ, int32_t* MAPX, int32_t* MAPY, void* MAPV) {
+    int64_t* perm = (int64_t*)malloc(sizeof(int64_t) * (size_t)(nnz > 0 ? nnz : 1));
+    int rc = oracle_map_order(X, Y, Z, nnz, mx, my, mz, perm);
+    if (rc) {
+        free(perm);
+        return rc;
+    }
+    const char* vin = (const char*)mv;
+    char* vout = (char*)MAPV;
+    int64_t p = 0, e = 0;
+    while (e < nnz) {
+        const int32_t z = mz[perm[e]];
+        int64_t end = e;
+        while (end < nnz && mz[perm[end]] == z) ++end;
+        while (e < end) {
+            MAPZ[p] = z;
+            int32_t last_x = 0, last_y = 0;
+            for (int64_t q = 0; q < g; ++q) {
+                if (e < end) {
+                    last_x = mx[perm[e]];
+                    last_y = my[perm[e]];
+                    memcpy(vout + (size_t)(p * g + q) * elem_size, vin + (size_t)perm[e] * elem_size,
+                           (size_t)elem_size);
+                    ++e;
+                } else {
+                    memset(vout + (size_t)(p * g + q) * elem_size, 0, (size_t)elem_size);
+                }
+                MAPX[p * g + q] = last_x;
+                MAPY[p * g + q] = last_y;
+            }
+            ++p;
+        }
+    }
+    free(perm);
+    return 0;
+}
+
+/* Out[MAPX[p,q], m] += MAPV[p,q] * sum_c In[MAPY[p,q], c] * W[MAPZ[p], c, m]  in fp64.
+ * Out is not cleared here.  Threads own disjoint ranges of m. */
+void oracle_spconv_groupcoo(int64_t C, int64_t M, int64_t G, int64_t g, const int32_t* MAPZ,
+                            const int32_t* MAPX, const int32_t* MAPY, const float* MAPV,
+                            const float* In, int64_t ld_in, const float* W, double* Out,
+                            int64_t ld_out) {
+#pragma omp parallel
+    {
+        int64_t m0, m1;
+        column_slice(M, &m0, &m1);
+        for (int64_t p = 0; p < G; ++p)
+            for (int64_t q = 0; q < g; ++q) {
+                const double v = (double)MAPV[p * g + q];
+                const float* in = In + (int64_t)MAPY[p * g + q] * ld_in;
+                const float* w = W + (int64_t)MAPZ[p] * C * M;
+                double* out = Out + (int64_t)MAPX[p * g + q] * ld_out;
+                for (int64_t m = m0; m < m1; ++m) {
+                    double acc = 0.0;
+                    for (int64_t c = 0; c < C; ++c) acc += (double)in[c] * (double)w[c * M + m];
+                    out[m] += v * acc;
+                }
+            }
     }
 }
 

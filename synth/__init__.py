@@ -14,5 +14,6 @@ from .workloads import (  # noqa: F401
     random_coo,
     round_to_dtype,
     storage_array,
+    voxel_kernel_map,
     zipf_rows_coo,
 )

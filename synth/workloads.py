@@ -175,6 +175,45 @@ def random_block_coo(M: int, K: int, bM: int, bK: int, seed: int, dtype: str = "
     return row, col, val
 
 
+def voxel_kernel_map(grid: int, density: float, seed: int, kernel: int = 3, dtype: str = "f16",
+                     values: str = "ones", shuffle: bool = True):
+    """Kernel map of a submanifold sparse convolution on a synthetic point cloud: voxels of a
+    grid^3 volume are occupied independently with probability `density`; for every occupied
+    voxel x and every offset z of the kernel^3 stencil whose neighbour y is occupied the map
+    holds the entry (x, y, z).  Stands in for the voxelised indoor scans of Section 6.4.
+    Returns (P, mx, my, mz, mv): number of points and the COO arrays of Map[x, y, z]."""
+    r_pos, r_val, _, r_perm = _streams(seed)
+    occ = r_pos.random((grid, grid, grid)) < density
+    coords = np.argwhere(occ).astype(np.int64)                     # [P, 3], lexicographic
+    P = coords.shape[0]
+    half = kernel // 2
+    index = -np.ones((grid + 2 * half,) * 3, dtype=np.int64)       # lookup table with a halo
+    index[coords[:, 0] + half, coords[:, 1] + half, coords[:, 2] + half] = np.arange(P)
+    xs, ys, zs = [], [], []
+    z = 0
+    for dx in range(-half, half + 1):
+        for dy in range(-half, half + 1):
+            for dz in range(-half, half + 1):
+                nb = index[coords[:, 0] + half + dx, coords[:, 1] + half + dy, coords[:, 2] + half + dz]
+                hit = nb >= 0
+                xs.append(np.flatnonzero(hit))
+                ys.append(nb[hit])
+                zs.append(np.full(int(hit.sum()), z))
+                z += 1
+    mx = np.concatenate(xs).astype(np.int32)
+    my = np.concatenate(ys).astype(np.int32)
+    mz = np.concatenate(zs).astype(np.int32)
+    if values == "ones":
+        mv = np.ones(mx.shape[0], dtype=np.float32)
+    else:
+        mv = r_val.normal(0.0, 1.0, size=mx.shape[0]).astype(np.float32)
+    mv = round_to_dtype(mv, dtype)
+    if shuffle:
+        perm = r_perm.permutation(mx.shape[0])
+        mx, my, mz, mv = mx[perm], my[perm], mz[perm], mv[perm]
+    return P, mx, my, mz, mv
+
+
 def dense_operand(K: int, N: int, seed: int, dtype: str) -> np.ndarray:
     rng = _streams(seed)[2]
     return round_to_dtype(rng.standard_normal((K, N), dtype=np.float32), dtype)
