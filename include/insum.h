@@ -193,6 +193,66 @@ insum_status insum_spmm_blockgroupcoo(int64_t M, int64_t K, int64_t N, int64_t G
                                       void* C, int64_t ldc, insum_dtype c_dt, int accumulate,
                                       void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---------------------------------------------------------------------------------- */
+/* Point-cloud sparse convolution (Section 6.4)                                        */
+/*   Out[MAPX[p,q], m] += MAPV[p,q] * In[MAPY[p,q], c] * Weight[MAPZ[p], c, m]         */
+/* The kernel map Map[x, y, z] (output point x receives input point y through kernel   */
+/* offset z) is a 3-D sparse tensor in COO, grouped along z with group size g.         */
+/* ---------------------------------------------------------------------------------- */
+
+size_t insum_map_to_groupcoo_workspace_bytes(int64_t Z, int64_t nnz);
+
+/*
+ * Groups a kernel map along its offset dimension.
+ *
+ *   mx, my, mz  device int32[nnz]  coordinates: 0 <= mx < X, 0 <= my < Y, 0 <= mz < Z, any
+ *                                  order, repeated triples stay separate entries
+ *   mv          device dt[nnz]     values (1 for a plain convolution); copied bit for bit
+ *   g           group size, or 0 for insum_default_group_size(nnz, Z)
+ *   MAPZ        device int32[capacity_groups]      offset of each group (non-decreasing)
+ *   MAPX, MAPY  device int32[capacity_groups * g]  output / input point of each slot, [G, g]
+ *   MAPV        device dt[capacity_groups * g]     values, [G, g]
+ *   workspace   device scratch, at least insum_map_to_groupcoo_workspace_bytes(Z, nnz)
+ *
+ * Layout produced: offsets ascending; inside an offset entries ascending by (x, input
+ * position); an offset with occ entries owns ceil(occ/g) consecutive groups; a padding slot
+ * (tail of the last group of an offset) has value +0 and repeats the x and y of the last
+ * real entry of its group.  G never exceeds nnz/g + min(Z, nnz).
+ * Count mode (MAPZ = MAPX = MAPY = MAPV = NULL), capacity behaviour, status codes and
+ * synchronisation as for insum_coo_to_groupcoo.
+ */
+insum_status insum_map_to_groupcoo(int64_t X, int64_t Y, int64_t Z, int64_t nnz,
+                                   const int32_t* mx, const int32_t* my, const int32_t* mz,
+                                   const void* mv, insum_dtype dt, int32_t g,
+                                   int32_t* g_used, int64_t* num_groups,
+                                   int32_t* MAPZ, int32_t* MAPX, int32_t* MAPY, void* MAPV,
+                                   int64_t capacity_groups,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Out = conv (accumulate == 0) or Out += conv (accumulate != 0) with the grouped map above.
+ *
+ *   MAPZ, MAPX, MAPY, MAPV  device; layout as produced by insum_map_to_groupcoo (MAPZ
+ *               non-decreasing is not required; coordinates are not checked)
+ *   In          device dt[Y, ld_in]   input features, C channels per point, ld_in >= C
+ *   W           device dt[Z, C, M]    one C x M weight matrix per kernel offset, m fastest
+ *   dt          type of MAPV, In and W: F32, F16 or BF16
+ *   Out         device float[X, ld_out]  output features, M channels per point, fp32
+ *
+ * Products and sums are formed in fp32 (on the matrix cores for the 16-bit types when C is
+ * a multiple of 8 and at most 256, ld_in is a multiple of 8 and In is 16-byte aligned; a
+ * slower general kernel otherwise) and added to Out with hardware fp32 atomics, in an order
+ * that differs from run to run: results are reproducible up to fp32 summation order.
+ * accumulate == 0 first sets Out[0:X, 0:M] to zero.  A slot with value zero contributes
+ * nothing; In and W are assumed finite.  No workspace.  Asynchronous.
+ */
+insum_status insum_spconv_groupcoo(int64_t X, int64_t Y, int64_t Z, int64_t C, int64_t M,
+                                   int64_t G, int32_t g,
+                                   const int32_t* MAPZ, const int32_t* MAPX, const int32_t* MAPY,
+                                   const void* MAPV, const void* In, int64_t ld_in, const void* W,
+                                   insum_dtype dt, float* Out, int64_t ld_out, int accumulate,
+                                   void* stream);
+
 #ifdef __cplusplus
 }
 #endif

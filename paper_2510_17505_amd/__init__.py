@@ -1,4 +1,5 @@
-"""MI355X-native SpMM over the Insum fixed-length sparse formats (GroupCOO, BlockGroupCOO).
+"""MI355X-native SpMM over the Insum fixed-length sparse formats (GroupCOO, BlockGroupCOO),
+and point-cloud sparse convolution over a kernel map grouped the same way.
 
 Thin Python binding of ``libinsum.so``: the functions below only marshal arguments
 (device pointers of torch tensors, sizes, the current HIP stream) into the C ABI declared
@@ -10,10 +11,14 @@ from .api import (  # noqa: F401
     BlockGroupCOO,
     GroupCOO,
     InsumError,
+    MapGroupCOO,
     insum_coo_to_blockgroupcoo,
     insum_coo_to_groupcoo,
     insum_default_group_size,
     insum_indirect_access_cost,
+    insum_map_count_groups,
+    insum_map_to_groupcoo,
+    insum_spconv_groupcoo,
     insum_spmm_blockgroupcoo,
     insum_spmm_blockgroupcoo_workspace_bytes,
     insum_spmm_groupcoo,

@@ -12,7 +12,7 @@ OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libinsum.so")
 PEAKS_LIB = os.path.join(PKG, "libinsum_peaks.so")   # achievable-peak microbenchmarks (bench.py --peaks)
 
-SOURCES = ["misc.cpp", "convert.hip", "spmm_groupcoo.hip", "spmm_blockgroupcoo.hip"]
+SOURCES = ["misc.cpp", "convert.hip", "spmm_groupcoo.hip", "spmm_blockgroupcoo.hip", "spconv_groupcoo.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -43,7 +43,7 @@ def _compile(src: str) -> str:
 def build(verbose: bool = False) -> str:
     """Compile every source (always) and link the shared library."""
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=5) as ex:
+    with ThreadPoolExecutor(max_workers=6) as ex:
         objs = list(ex.map(_compile, SOURCES + ["peaks.hip"]))
     peaks_obj = objs.pop()
     res = subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", PEAKS_LIB, peaks_obj],

@@ -56,6 +56,13 @@ _sb_ws = _sig("insum_spmm_blockgroupcoo_workspace_bytes", C.c_size_t,
 _sb = _sig("insum_spmm_blockgroupcoo", C.c_int,
            [_i64, _i64, _i64, _i64, _i32, _i32, _i32, _p, _p, _p, C.c_int, _p, _i64, C.c_int,
             _p, _i64, C.c_int, C.c_int, _p, C.c_size_t, _p])
+_m_ws = _sig("insum_map_to_groupcoo_workspace_bytes", C.c_size_t, [_i64, _i64])
+_m_conv = _sig("insum_map_to_groupcoo", C.c_int,
+               [_i64, _i64, _i64, _i64, _p, _p, _p, _p, C.c_int, _i32, _p, _p, _p, _p, _p, _p, _i64,
+                _p, C.c_size_t, _p])
+_conv = _sig("insum_spconv_groupcoo", C.c_int,
+             [_i64, _i64, _i64, _i64, _i64, _i64, _i32, _p, _p, _p, _p, _p, _i64, _p, C.c_int,
+              _p, _i64, C.c_int, _p])
 
 
 class InsumError(RuntimeError):
@@ -130,6 +137,22 @@ class BlockGroupCOO:
     @property
     def G(self) -> int:
         return int(self.AM.shape[0])
+
+
+@dataclass
+class MapGroupCOO:
+    X: int
+    Y: int
+    Z: int
+    g: int
+    MAPZ: torch.Tensor   # int32 [G]      kernel offset of each group
+    MAPX: torch.Tensor   # int32 [G, g]   output points
+    MAPY: torch.Tensor   # int32 [G, g]   input points
+    MAPV: torch.Tensor   # dtype [G, g]
+
+    @property
+    def G(self) -> int:
+        return int(self.MAPZ.shape[0])
 
 
 def insum_coo_to_groupcoo(M: int, K: int, row, col, val, g: int = 0) -> GroupCOO:
@@ -226,3 +249,57 @@ def insum_spmm_blockgroupcoo(A: BlockGroupCOO, B: torch.Tensor, C_out: torch.Ten
              0 if workspace is None else workspace.numel(), _stream())
     _check(st, "insum_spmm_blockgroupcoo")
     return C_out
+
+
+def insum_map_to_groupcoo(X: int, Y: int, Z: int, mx, my, mz, mv, g: int = 0) -> MapGroupCOO:
+    """Groups the kernel map Map[x, y, z] of a sparse convolution along its offsets z."""
+    mx, my, mz, mv = _dev(mx, "mx"), _dev(my, "my"), _dev(mz, "mz"), _dev(mv, "mv")
+    assert mx.dtype == my.dtype == mz.dtype == torch.int32 and mv.dtype in _DTYPE
+    nnz = mx.numel()
+    assert my.numel() == nnz and mz.numel() == nnz and mv.numel() == nnz
+    dev = mv.device
+    ws = torch.empty(int(_m_ws(Z, nnz)), dtype=torch.uint8, device=dev)
+    g_used, G = _i32(0), _i64(0)
+    g_eff = int(g) if g else insum_default_group_size(nnz, Z)
+    cap = nnz // g_eff + min(Z, nnz)            # bound on G stated in insum.h
+    MAPZ = torch.empty(cap, dtype=torch.int32, device=dev)
+    MAPX = torch.empty((cap, g_eff), dtype=torch.int32, device=dev)
+    MAPY = torch.empty((cap, g_eff), dtype=torch.int32, device=dev)
+    MAPV = torch.empty((cap, g_eff), dtype=mv.dtype, device=dev)
+    if nnz:
+        _check(_m_conv(X, Y, Z, nnz, _ptr(mx), _ptr(my), _ptr(mz), _ptr(mv), _DTYPE[mv.dtype], int(g),
+                       C.addressof(g_used), C.addressof(G), _ptr(MAPZ), _ptr(MAPX), _ptr(MAPY), _ptr(MAPV),
+                       cap, _ptr(ws), ws.numel(), _stream()), "insum_map_to_groupcoo")
+    else:
+        g_used.value = g_eff
+    n = G.value
+    return MapGroupCOO(X, Y, Z, g_used.value, MAPZ[:n], MAPX[:n], MAPY[:n], MAPV[:n])
+
+
+def insum_map_count_groups(X: int, Y: int, Z: int, mx, my, mz, g: int = 0):
+    """Count mode of insum_map_to_groupcoo: returns (g_used, G) without writing the format."""
+    nnz = mx.numel()
+    ws = torch.empty(int(_m_ws(Z, nnz)), dtype=torch.uint8, device=mx.device)
+    g_used, G = _i32(0), _i64(0)
+    dummy = torch.zeros(max(nnz, 1), dtype=torch.float16, device=mx.device)
+    _check(_m_conv(X, Y, Z, nnz, _ptr(mx), _ptr(my), _ptr(mz), _ptr(dummy), 1, int(g),
+                   C.addressof(g_used), C.addressof(G), 0, 0, 0, 0, 0, _ptr(ws), ws.numel(), _stream()),
+           "insum_map_to_groupcoo(count)")
+    return g_used.value, G.value
+
+
+def insum_spconv_groupcoo(Map: MapGroupCOO, In: torch.Tensor, W: torch.Tensor,
+                          Out: torch.Tensor | None = None, accumulate: bool = False) -> torch.Tensor:
+    """Out[MAPX[p,q], m] (+)= MAPV[p,q] * In[MAPY[p,q], c] * W[MAPZ[p], c, m]; Out is fp32 [X, M]."""
+    assert In.is_cuda and In.dim() == 2 and In.shape[0] == Map.Y and In.stride(1) == 1
+    assert W.is_cuda and W.dim() == 3 and W.is_contiguous() and W.shape[0] == Map.Z
+    assert W.shape[1] == In.shape[1] and W.dtype == In.dtype
+    assert Map.G == 0 or Map.MAPV.dtype == In.dtype
+    Cc, M = int(W.shape[1]), int(W.shape[2])
+    Out = _out(Out, Map.X, M, torch.float32, In.device, accumulate)
+    assert Out.dtype == torch.float32
+    st = _conv(Map.X, Map.Y, Map.Z, Cc, M, Map.G, Map.g, _ptr(Map.MAPZ), _ptr(Map.MAPX), _ptr(Map.MAPY),
+               _ptr(Map.MAPV), _ptr(In), In.stride(0), _ptr(W), _DTYPE[In.dtype], _ptr(Out), Out.stride(0),
+               int(bool(accumulate)), _stream())
+    _check(st, "insum_spconv_groupcoo")
+    return Out

@@ -15,6 +15,10 @@
 // instead of the sort.  Values are moved as raw bits; there is no floating-point arithmetic,
 // so the output is a pure function of the input.
 //
+// The kernel map of a sparse convolution (Section 6.4) is grouped along its offset z the same
+// way: key = z*X + x, the sort carries (y, value bits) packed in 64 bits, and the offsets play
+// the part of the rows.
+//
 // The device-wide sort and prefix sums are rocPRIM's (library primitives); everything
 // specific to the formats is in the kernels of this file.
 #include <cstring>
@@ -81,6 +85,7 @@ size_t sort_temp_bytes_v(int64_t nnz) {
 size_t sort_temp_bytes(int64_t nnz) {
     return std::max(sort_temp_bytes_v<uint32_t>(nnz), sort_temp_bytes_v<uint16_t>(nnz));
 }
+size_t sort_temp_bytes_map(int64_t nnz) { return sort_temp_bytes_v<uint64_t>(nnz); }
 
 size_t scan_temp_bytes(int64_t n) {
     size_t bytes = 0;
@@ -250,6 +255,77 @@ __global__ void k_block_fill(Divisor per_block, Divisor blocks_per_row, int64_t 
         if (slot == 0) AM[grp] = (int32_t)br;
         if (rank == occ - 1)
             for (int32_t q = slot + 1; q < g; ++q) AK[grp * g + q] = bc;
+    }
+}
+
+// ---- kernels: kernel map grouped along z -------------------------------------------------------
+constexpr int kLdsBins = 4096;  // offsets counted in LDS when Z is at most this
+
+// Validates the coordinates.  Fill mode forms key = z*X + x and payload = (y << 32) | value
+// bits.  Count mode adds to occ[z]: per work-group in LDS first when Z <= kLdsBins (a stencil
+// has few offsets, so global atomics would all hit the same few words).
+template <typename V, bool HISTOGRAM>
+__global__ void k_map_keys(int64_t X, int64_t Y, int64_t Z, int64_t nnz, const int32_t* __restrict__ mx,
+                           const int32_t* __restrict__ my, const int32_t* __restrict__ mz,
+                           const V* __restrict__ mv, uint64_t* __restrict__ key,
+                           uint64_t* __restrict__ payload, int32_t* __restrict__ occ, Flags* flags) {
+    __shared__ int32_t bins[HISTOGRAM ? kLdsBins : 1];
+    const bool lds = HISTOGRAM && Z <= kLdsBins;
+    if constexpr (HISTOGRAM) {
+        if (lds) {
+            for (int b = threadIdx.x; b < Z; b += kThreads) bins[b] = 0;
+            __syncthreads();
+        }
+    }
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < nnz) {
+        const int32_t x = mx[i], y = my[i], z = mz[i];
+        const bool ok = x >= 0 && x < X && y >= 0 && y < Y && z >= 0 && z < Z;
+        if (!ok) flags->out_of_range = 1;
+        if constexpr (HISTOGRAM) {
+            if (ok) atomicAdd(lds ? &bins[z] : &occ[z], 1);
+        } else {
+            key[i] = ok ? (uint64_t)z * (uint64_t)X + (uint64_t)x : 0;
+            payload[i] = ((uint64_t)(uint32_t)y << 32) | (uint64_t)mv[i];
+        }
+    }
+    if constexpr (HISTOGRAM) {
+        if (lds) {
+            __syncthreads();
+            for (int b = threadIdx.x; b < Z; b += kThreads)
+                if (bins[b]) atomicAdd(&occ[b], bins[b]);
+        }
+    }
+}
+
+template <typename V>
+__global__ void k_map_fill(Divisor per_z, int64_t nnz, int32_t g, const uint64_t* __restrict__ key,
+                           const uint64_t* __restrict__ payload, const int32_t* __restrict__ z_start,
+                           const int32_t* __restrict__ grp_start, int32_t* __restrict__ MAPZ,
+                           int32_t* __restrict__ MAPX, int32_t* __restrict__ MAPY, V* __restrict__ MAPV) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= nnz) return;
+    const uint64_t k = key[i];
+    const uint64_t pl = payload[i];
+    const int64_t z = (int64_t)per_z.div(k);
+    const int32_t x = (int32_t)(k - (uint64_t)z * per_z.d);
+    const int32_t y = (int32_t)(pl >> 32);
+    const int32_t first = z_start[z];
+    const int32_t rank = (int32_t)(i - first);
+    const int32_t occ = z_start[z + 1] - first;
+    const int64_t grp = (int64_t)grp_start[z] + rank / g;
+    const int32_t slot = rank % g;
+    const int64_t dst = grp * g + slot;
+    MAPX[dst] = x;
+    MAPY[dst] = y;
+    MAPV[dst] = (V)pl;
+    if (slot == 0) MAPZ[grp] = (int32_t)z;
+    if (rank == occ - 1) {  // last entry of its offset: pad the rest of the group
+        for (int32_t q = slot + 1; q < g; ++q) {
+            MAPX[grp * g + q] = x;
+            MAPY[grp * g + q] = y;
+            MAPV[grp * g + q] = (V)0;
+        }
     }
 }
 
@@ -492,6 +568,101 @@ extern "C" insum_status insum_coo_to_blockgroupcoo(int64_t M, int64_t K, int64_t
                            blocks_per_row, nnz, g, key_b, reinterpret_cast<const uint16_t*>(val_b), head,
                            blk_ord, brow_start, grp_start, AM, AK, static_cast<uint16_t*>(AV));
     }
+    INSUM_HIP_TRY(hipGetLastError());
+    INSUM_HIP_TRY(hipStreamSynchronize(s));
+    return INSUM_OK;
+}
+
+// ============================================================================================
+extern "C" size_t insum_map_to_groupcoo_workspace_bytes(int64_t Z, int64_t nnz) {
+    Z = std::max<int64_t>(Z, 0);
+    nnz = std::max<int64_t>(nnz, 0);
+    const size_t n1 = (size_t)std::max<int64_t>(nnz, 1);
+    size_t b = 512;
+    b += align_up(sizeof(Flags), 256);
+    b += 3 * align_up((size_t)(Z + 1) * 4, 256);  // groups per offset, z_start, grp_start
+    b += 4 * align_up(n1 * 8, 256);               // keys in/out, payloads in/out
+    b += align_up(std::max(sort_temp_bytes_map(nnz), scan_temp_bytes(Z + 1)), 256);
+    return b;
+}
+
+extern "C" insum_status insum_map_to_groupcoo(int64_t X, int64_t Y, int64_t Z, int64_t nnz,
+                                              const int32_t* mx, const int32_t* my, const int32_t* mz,
+                                              const void* mv, insum_dtype dt, int32_t g, int32_t* g_used,
+                                              int64_t* num_groups, int32_t* MAPZ, int32_t* MAPX,
+                                              int32_t* MAPY, void* MAPV, int64_t capacity_groups,
+                                              void* workspace, size_t workspace_bytes, void* stream) {
+    if (X < 0 || Y < 0 || Z < 0 || nnz < 0 || g < 0 || !g_used || !num_groups) return INSUM_ERR_INVALID_ARG;
+    if (X >= (1LL << 31) || Y >= (1LL << 31) || Z >= (1LL << 31) || nnz >= (1LL << 31))
+        return INSUM_ERR_INVALID_ARG;
+    if (!dtype_valid(dt)) return INSUM_ERR_INVALID_ARG;
+    if (nnz > 0 && (!mx || !my || !mz || !mv)) return INSUM_ERR_INVALID_ARG;
+    const bool fill = MAPZ || MAPX || MAPY || MAPV;
+    if (fill && (!MAPZ || !MAPX || !MAPY || !MAPV || capacity_groups < 0)) return INSUM_ERR_INVALID_ARG;
+    if (g == 0) g = insum_default_group_size(nnz, Z);
+    *g_used = g;
+    *num_groups = 0;
+    if (nnz == 0) return INSUM_OK;
+    if (X == 0 || Y == 0 || Z == 0) return INSUM_ERR_OUT_OF_RANGE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    Carver ws(workspace, workspace_bytes);
+    Flags* d_flags = ws.take<Flags>(1);
+    int32_t* gpz = ws.take<int32_t>(Z + 1);  // per-offset counts, then groups per offset
+    int32_t* z_start = ws.take<int32_t>(Z + 1);
+    int32_t* grp_start = ws.take<int32_t>(Z + 1);
+    uint64_t* key_a = ws.take<uint64_t>(nnz);
+    uint64_t* key_b = ws.take<uint64_t>(nnz);
+    uint64_t* pay_a = ws.take<uint64_t>(nnz);
+    uint64_t* pay_b = ws.take<uint64_t>(nnz);
+    const size_t temp_bytes = std::max(sort_temp_bytes_map(nnz), scan_temp_bytes(Z + 1));
+    void* temp = ws.take<char>(temp_bytes);
+    if (!ws.ok) return INSUM_ERR_CAPACITY;
+
+    const Divisor per_z((uint64_t)X);
+    const bool wide = dtype_size(dt) == 4;
+    const dim3 grid_nnz(blocks_for(nnz)), block(kThreads);
+    insum_status st;
+    hipLaunchKernelGGL(k_zero_i32, dim3(1), block, 0, s, reinterpret_cast<int32_t*>(d_flags),
+                       (int64_t)(sizeof(Flags) / 4));
+    if (!fill) {
+        hipLaunchKernelGGL(k_zero_i32, dim3(blocks_for(Z + 1)), block, 0, s, gpz, Z + 1);
+        hipLaunchKernelGGL((k_map_keys<uint16_t, true>), grid_nnz, block, 0, s, X, Y, Z, nnz, mx, my, mz,
+                           static_cast<const uint16_t*>(nullptr), key_a, pay_a, gpz, d_flags);
+        hipLaunchKernelGGL(k_groups_from_counts, dim3(blocks_for(Z + 1)), block, 0, s, Z, gpz, g);
+    } else {
+        if (wide)
+            hipLaunchKernelGGL((k_map_keys<uint32_t, false>), grid_nnz, block, 0, s, X, Y, Z, nnz, mx, my, mz,
+                               static_cast<const uint32_t*>(mv), key_a, pay_a, gpz, d_flags);
+        else
+            hipLaunchKernelGGL((k_map_keys<uint16_t, false>), grid_nnz, block, 0, s, X, Y, Z, nnz, mx, my, mz,
+                               static_cast<const uint16_t*>(mv), key_a, pay_a, gpz, d_flags);
+        INSUM_HIP_TRY(hipGetLastError());
+        const int key_bits = bits_for((uint64_t)Z * (uint64_t)X - 1);
+        st = sort_by_key<uint64_t>(temp, temp_bytes, key_a, key_b, pay_a, pay_b, nnz, key_bits, s);
+        if (st != INSUM_OK) return st;
+        hipLaunchKernelGGL(k_row_bounds, dim3(blocks_for(nnz + 1)), block, 0, s, nnz, Z, per_z, key_b, z_start);
+        hipLaunchKernelGGL(k_groups_from_bounds, dim3(blocks_for(Z + 1)), block, 0, s, Z, z_start, g, gpz);
+    }
+    st = scan_exclusive(temp, temp_bytes, gpz, grp_start, Z + 1, s);
+    if (st != INSUM_OK) return st;
+    hipLaunchKernelGGL(k_store_total, dim3(1), dim3(1), 0, s, grp_start + Z, &d_flags->total_a);
+    INSUM_HIP_TRY(hipGetLastError());
+    Flags h;
+    st = read_flags(d_flags, &h, s);
+    if (st != INSUM_OK) return st;
+    if (h.out_of_range) return INSUM_ERR_OUT_OF_RANGE;
+    const int64_t G = h.total_a;
+    *num_groups = G;
+    if (!fill) return INSUM_OK;
+    if (capacity_groups < G) return INSUM_ERR_CAPACITY;
+
+    if (wide)
+        hipLaunchKernelGGL(k_map_fill<uint32_t>, grid_nnz, block, 0, s, per_z, nnz, g, key_b, pay_b, z_start,
+                           grp_start, MAPZ, MAPX, MAPY, static_cast<uint32_t*>(MAPV));
+    else
+        hipLaunchKernelGGL(k_map_fill<uint16_t>, grid_nnz, block, 0, s, per_z, nnz, g, key_b, pay_b, z_start,
+                           grp_start, MAPZ, MAPX, MAPY, static_cast<uint16_t*>(MAPV));
     INSUM_HIP_TRY(hipGetLastError());
     INSUM_HIP_TRY(hipStreamSynchronize(s));
     return INSUM_OK;
