@@ -121,6 +121,50 @@ def run_workload(torch, I, name, steps, warmup):
     return res, (cfg, A, B, C)
 
 
+SPCONV = {"grid": 96, "density": 0.3, "C": 128, "M": 128, "dtype": "f16"}
+
+
+def run_spconv(torch, I, steps, warmup):
+    """Point-cloud sparse convolution (Section 6.4) on a synthetic voxel kernel map: 3x3x3
+    stencil over a 96^3 grid with 30 % of the voxels occupied, 128 -> 128 channels, fp16
+    features and weights, fp32 output.  Timed like the SpMM workloads (map already grouped)."""
+    import synth
+    c = SPCONV
+    P, mx, my, mz, mv = synth.voxel_kernel_map(c["grid"], c["density"], seed=0, dtype=c["dtype"])
+    rng = np.random.default_rng(1)
+    In = _to_device(torch, synth.round_to_dtype(rng.normal(size=(P, c["C"])).astype(np.float32), c["dtype"]),
+                    c["dtype"])
+    W = _to_device(torch, synth.round_to_dtype((rng.normal(size=(27, c["C"], c["M"])) / 8).astype(np.float32),
+                                               c["dtype"]), c["dtype"])
+    dmx, dmy, dmz = (torch.from_numpy(a).cuda() for a in (mx, my, mz))
+    dmv = _to_device(torch, mv, c["dtype"])
+    conv_ms = None
+    for _ in range(2):
+        Map = None
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        Map = I.insum_map_to_groupcoo(P, P, 27, dmx, dmy, dmz, dmv, g=0)
+        torch.cuda.synchronize()
+        conv_ms = (time.perf_counter() - t0) * 1e3
+    Out = torch.empty((P, c["M"]), dtype=torch.float32, device="cuda")
+    ms = _time_launches(torch, lambda: I.insum_spconv_groupcoo(Map, In, W, Out=Out), steps, warmup)
+    S = int(mx.shape[0])
+    slots = Map.G * Map.g
+    flops = 2.0 * S * c["C"] * c["M"]
+    # per slot: one gathered input row, one fp32 output row added to (read + write), x, y, value;
+    # plus the zero-fill of Out and the weights
+    model_bytes = slots * (c["C"] * 2 + 2 * c["M"] * 4 + 4 + 4 + 2) + 4 * Map.G + P * c["M"] * 4 \
+        + 27 * c["C"] * c["M"] * 2
+    tf = flops / ms / 1e9
+    return {"format": "GroupCOO along the kernel offset", "dtype": c["dtype"], "points": P, "nnz": S,
+            "C": c["C"], "M": c["M"], "g": Map.g, "groups": Map.G, "ms_per_step": ms, "tflops": tf,
+            "model_bytes": int(model_bytes), "model_gbs": model_bytes / ms / 1e6, "conversion_ms": conv_ms,
+            "roofline": {"bound": "hbm", "achieved": model_bytes / ms / 1e6, "peak": HBM_PEAK_GBS,
+                         "unit": "GB/s", "frac": model_bytes / ms / 1e6 / HBM_PEAK_GBS,
+                         "traffic": _traffic("spconv"),
+                         "mfma_frac": tf / MFMA_PEAK_TFLOPS}}
+
+
 def _traffic(name):
     """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
@@ -270,6 +314,8 @@ def main():
                     help="only run the group-size sweep on the paper's ablation shape")
     ap.add_argument("--context", action="store_true",
                     help="only time the vendor libraries PyTorch dispatches to (context, not product)")
+    ap.add_argument("--spconv", action="store_true",
+                    help="only time the sparse-convolution workload (Section 6.4)")
     ap.add_argument("--peaks", action="store_true", help="only run the achievable-peak microbenchmarks")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="only run a plain elementwise copy of MIB mebibytes (read MIB, write MIB) "
@@ -299,6 +345,9 @@ def main():
         return
     if args.context:
         print(json.dumps({"vendor_context": vendor_context(torch, I, args.steps, args.warmup)}))
+        return
+    if args.spconv:
+        print(json.dumps({"spconv": run_spconv(torch, I, args.steps, args.warmup)}))
         return
     if args.sweep:
         print(json.dumps({"group_size_sweep": group_size_sweep(torch, I, args.steps, args.warmup)}))
@@ -330,6 +379,7 @@ def main():
             torch.cuda.empty_cache()
             others[name] = {k: r[k] for k in ("format", "dtype", "nnz", "N", "g", "ms_per_step", "gflops",
                                               "model_gbs", "roofline", "conversion_ms")}
+        others["spconv"] = run_spconv(torch, I, args.steps, args.warmup)
         line["other_workloads"] = others
         line["measured_peaks"] = measured_peaks()
     print(json.dumps(line))

@@ -229,29 +229,39 @@ insum_status insum_map_to_groupcoo(int64_t X, int64_t Y, int64_t Z, int64_t nnz,
                                    int64_t capacity_groups,
                                    void* workspace, size_t workspace_bytes, void* stream);
 
+/* Bytes of device workspace insum_spconv_groupcoo needs for these sizes (an inverse table of
+ * the map, transposed weights and a list of repeated (x, z) pairs); 0 when the shape runs on
+ * the scatter kernels, which need none.  Host only. */
+size_t insum_spconv_groupcoo_workspace_bytes(int64_t X, int64_t Z, int64_t C, int64_t M,
+                                             int64_t G, int32_t g, insum_dtype dt);
+
 /*
  * Out = conv (accumulate == 0) or Out += conv (accumulate != 0) with the grouped map above.
  *
- *   MAPZ, MAPX, MAPY, MAPV  device; layout as produced by insum_map_to_groupcoo (MAPZ
- *               non-decreasing is not required; coordinates are not checked)
+ *   MAPZ, MAPX, MAPY, MAPV  device; layout as produced by insum_map_to_groupcoo (any order of
+ *               groups and slots is accepted; coordinates are not checked)
  *   In          device dt[Y, ld_in]   input features, C channels per point, ld_in >= C
  *   W           device dt[Z, C, M]    one C x M weight matrix per kernel offset, m fastest
  *   dt          type of MAPV, In and W: F32, F16 or BF16
  *   Out         device float[X, ld_out]  output features, M channels per point, fp32
+ *   workspace   device scratch, at least insum_spconv_groupcoo_workspace_bytes(...) bytes
+ *               (INSUM_ERR_CAPACITY otherwise); may be NULL when that is 0
  *
- * Products and sums are formed in fp32 (on the matrix cores for the 16-bit types when C is
- * a multiple of 8 and at most 256, ld_in is a multiple of 8 and In is 16-byte aligned; a
- * slower general kernel otherwise) and added to Out with hardware fp32 atomics, in an order
- * that differs from run to run: results are reproducible up to fp32 summation order.
- * accumulate == 0 first sets Out[0:X, 0:M] to zero.  A slot with value zero contributes
- * nothing; In and W are assumed finite.  No workspace.  Asynchronous.
+ * Products are exact and sums are formed in fp32.  16-bit types with C a multiple of 8, at
+ * most 256, ld_in a multiple of 8 and In 16-byte aligned run on the matrix cores, in one of
+ * two schedules: when the map holds at least X*Z/16 slots, by output point with the sums
+ * kept in registers and stored once (only repeated (x, z) pairs use atomics); otherwise by
+ * slot with fp32 atomic adds into Out.  Everything else runs on a general scatter kernel.
+ * The order of the fp32 additions differs between schedules and, where atomics are used,
+ * from run to run: results are reproducible up to fp32 summation order.
+ * A slot with value zero contributes nothing; In and W are assumed finite.  Asynchronous.
  */
 insum_status insum_spconv_groupcoo(int64_t X, int64_t Y, int64_t Z, int64_t C, int64_t M,
                                    int64_t G, int32_t g,
                                    const int32_t* MAPZ, const int32_t* MAPX, const int32_t* MAPY,
                                    const void* MAPV, const void* In, int64_t ld_in, const void* W,
                                    insum_dtype dt, float* Out, int64_t ld_out, int accumulate,
-                                   void* stream);
+                                   void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -19,6 +19,7 @@ from .api import (  # noqa: F401
     insum_map_count_groups,
     insum_map_to_groupcoo,
     insum_spconv_groupcoo,
+    insum_spconv_groupcoo_workspace_bytes,
     insum_spmm_blockgroupcoo,
     insum_spmm_blockgroupcoo_workspace_bytes,
     insum_spmm_groupcoo,

@@ -60,9 +60,11 @@ _m_ws = _sig("insum_map_to_groupcoo_workspace_bytes", C.c_size_t, [_i64, _i64])
 _m_conv = _sig("insum_map_to_groupcoo", C.c_int,
                [_i64, _i64, _i64, _i64, _p, _p, _p, _p, C.c_int, _i32, _p, _p, _p, _p, _p, _p, _i64,
                 _p, C.c_size_t, _p])
+_conv_ws = _sig("insum_spconv_groupcoo_workspace_bytes", C.c_size_t,
+                [_i64, _i64, _i64, _i64, _i64, _i32, C.c_int])
 _conv = _sig("insum_spconv_groupcoo", C.c_int,
              [_i64, _i64, _i64, _i64, _i64, _i64, _i32, _p, _p, _p, _p, _p, _i64, _p, C.c_int,
-              _p, _i64, C.c_int, _p])
+              _p, _i64, C.c_int, _p, C.c_size_t, _p])
 
 
 class InsumError(RuntimeError):
@@ -288,8 +290,13 @@ def insum_map_count_groups(X: int, Y: int, Z: int, mx, my, mz, g: int = 0):
     return g_used.value, G.value
 
 
+def insum_spconv_groupcoo_workspace_bytes(Map: MapGroupCOO, C_in: int, M_out: int, dtype) -> int:
+    return int(_conv_ws(Map.X, Map.Z, C_in, M_out, Map.G, Map.g, _DTYPE[dtype]))
+
+
 def insum_spconv_groupcoo(Map: MapGroupCOO, In: torch.Tensor, W: torch.Tensor,
-                          Out: torch.Tensor | None = None, accumulate: bool = False) -> torch.Tensor:
+                          Out: torch.Tensor | None = None, accumulate: bool = False,
+                          workspace=None) -> torch.Tensor:
     """Out[MAPX[p,q], m] (+)= MAPV[p,q] * In[MAPY[p,q], c] * W[MAPZ[p], c, m]; Out is fp32 [X, M]."""
     assert In.is_cuda and In.dim() == 2 and In.shape[0] == Map.Y and In.stride(1) == 1
     assert W.is_cuda and W.dim() == 3 and W.is_contiguous() and W.shape[0] == Map.Z
@@ -298,8 +305,12 @@ def insum_spconv_groupcoo(Map: MapGroupCOO, In: torch.Tensor, W: torch.Tensor,
     Cc, M = int(W.shape[1]), int(W.shape[2])
     Out = _out(Out, Map.X, M, torch.float32, In.device, accumulate)
     assert Out.dtype == torch.float32
+    nws = insum_spconv_groupcoo_workspace_bytes(Map, Cc, M, In.dtype)
+    if workspace is None and nws:
+        workspace = torch.empty(nws, dtype=torch.uint8, device=In.device)
     st = _conv(Map.X, Map.Y, Map.Z, Cc, M, Map.G, Map.g, _ptr(Map.MAPZ), _ptr(Map.MAPX), _ptr(Map.MAPY),
                _ptr(Map.MAPV), _ptr(In), In.stride(0), _ptr(W), _DTYPE[In.dtype], _ptr(Out), Out.stride(0),
-               int(bool(accumulate)), _stream())
+               int(bool(accumulate)), _ptr(workspace), 0 if workspace is None else workspace.numel(),
+               _stream())
     _check(st, "insum_spconv_groupcoo")
     return Out

@@ -266,6 +266,296 @@ __global__ void fill_zero_rows(float* out, int64_t rows, int64_t cols, int64_t l
     out[(i / cols) * ld + (i % cols)] = 0.f;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Output-stationary schedule.
+//
+// fp32 atomics complete at a fixed rate in the L2 (about two floats per clock and channel), which
+// bounds the scatter kernel above at roughly S*M / 6e11 seconds.  When the map is dense enough
+// (a few entries per 32 output points and offset) it is cheaper to walk the same grouped map
+// by output point: a work-group owns 128 consecutive output points and 64 output channels,
+// visits the offsets z = 0 .. Z-1 in turn, and keeps the sums in registers until they are
+// stored once.  Three small kernels prepare this per call, all in the caller's workspace:
+//   * table_fill / table_build invert the map into tabY[z][x] (input point or -1) and
+//     tabV[z][x]: one thread per slot claims its cell with a compare-and-swap.  A slot that
+//     finds the cell taken (the same (x, z) twice) goes to an overflow list.
+//   * weight_transpose writes Wt[z][m][c], zero-padded to whole tiles, so that the MFMA B
+//     fragment (8 consecutive channels of one output channel) is one 16-byte read.
+// spconv_os stages Wt[z] for its 64 output channels in LDS (double-buffered, rows swizzled so
+// that the 16-byte fragment reads of 16 neighbouring output channels hit all 64 banks once),
+// gathers the rows In[tabY[z][x]] straight into A fragments (absent points contribute zero
+// rows), runs the k-steps into a fresh accumulator and adds it, scaled by tabV, to the
+// running sums.  Table entries are read two offsets ahead and rows one offset ahead.
+// spconv_overflow then adds the overflow list's contributions with atomics.
+// ---------------------------------------------------------------------------------------------
+struct OsParams {
+    int64_t X, Z, C, M;
+    int64_t Xp;           // X rounded up to a multiple of 128 (table row length)
+    int32_t* tabY;        // [Z][Xp]
+    uint16_t* tabV;       // [Z][Xp]
+    uint16_t* Wt;         // [Z][Mp][Cp]
+    int64_t Mp;           // M rounded up to a multiple of 64
+    int32_t Cp;           // 16 * KS
+    int32_t* ovf_count;   // one counter
+    int32_t* ovf;         // [slots] slot ids
+    const void* In;
+    int64_t ld_in;
+    float* Out;
+    int64_t ld_out;
+    int32_t accumulate;
+    int32_t m_tiles, x_blocks;
+};
+
+__global__ void table_fill(int32_t* tabY, int64_t n, int32_t* ovf_count) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) tabY[i] = -1;
+    if (i == 0) *ovf_count = 0;
+}
+
+__global__ void table_build(ConvParams p, OsParams o) {
+    const int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (s >= p.slots) return;
+    const uint16_t vbits = static_cast<const uint16_t*>(p.MAPV)[s];
+    if ((vbits & 0x7fffu) == 0) return;  // +-0: padding or an explicit zero, contributes nothing
+    const int64_t cell = (int64_t)p.MAPZ[s / p.g] * o.Xp + p.MAPX[s];
+    if (atomicCAS(&o.tabY[cell], -1, p.MAPY[s]) == -1)
+        o.tabV[cell] = vbits;
+    else
+        o.ovf[atomicAdd(o.ovf_count, 1)] = (int32_t)s;
+}
+
+__global__ void weight_transpose(const uint16_t* __restrict__ W, OsParams o) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= o.Z * o.Mp * o.Cp) return;
+    const int64_t c = i % o.Cp, m = (i / o.Cp) % o.Mp, z = i / (o.Cp * o.Mp);
+    o.Wt[i] = (c < o.C && m < o.M) ? W[(z * o.C + c) * o.M + m] : (uint16_t)0;
+}
+
+// LDS position of 16-byte chunk ch of weight row n (CH chunks per row): the XOR spreads the rows
+// that one 16-lane read phase touches over all banks.
+template <int CH>
+__device__ inline int swizzled_chunk(int n, int ch) {
+    if constexpr (CH >= 16) return ch ^ (n % 16);
+    else return ch ^ ((n / (16 / CH)) % CH);
+}
+
+// (KS = 16 needs more than 256 registers for its two sets of A fragments: one wavefront per SIMD)
+template <typename T, int KS>
+__global__ __launch_bounds__(256, KS == 16 ? 1 : 2) void spconv_os(OsParams p) {
+    constexpr int NT = 2;                  // column blocks of 32 output channels per work-group
+    constexpr int CH = 2 * KS;             // 16-byte chunks per weight row
+    constexpr int ROWB = CH * 16;          // bytes per weight row in LDS
+    constexpr int TILE_CHUNKS = 32 * NT * CH;
+    constexpr int PER_THREAD = TILE_CHUNKS / 256;   // 1, 2, 4 or 8
+    constexpr int ROWS_PER_ROUND = 256 / CH;        // weight rows staged by one round of 256 threads
+    static_assert(TILE_CHUNKS % 256 == 0 && 256 % CH == 0, "staging assignment");
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2][32 * NT * ROWB];
+
+    // ids that share id % 8 run on one XCD: give the m-tiles of an x-block to the same one
+    const int64_t q = blockIdx.x / 8, xcd = blockIdx.x % 8;
+    const int64_t xblk = (q / p.m_tiles) * 8 + xcd;
+    const int mt = (int)(q % p.m_tiles);
+    if (xblk >= p.x_blocks) return;   // whole work-group leaves before any barrier
+
+    const int tid = threadIdx.x, lane = tid % 64, wv = tid / 64;
+    const int half = lane / 32, l32 = lane % 32;
+    const int m0 = mt * 32 * NT;
+    const int ksteps = (int)((p.C + 15) / 16);
+    const bool odd = p.C % 16 == 8;   // the last k-step holds 8 channels only
+    const uint16_t* const In = static_cast<const uint16_t*>(p.In);
+
+    // Table cells of this lane's output point, walked offset by offset.
+    const int32_t* tab_y = p.tabY + (xblk * 128 + wv * 32 + l32);
+    const uint16_t* tab_v = p.tabV + (xblk * 128 + wv * 32 + l32);
+
+    // Weight staging: thread owns chunk tid % CH of rows tid / CH + ROWS_PER_ROUND j.
+    const int st_n = tid / CH, st_ch = tid % CH;
+    const uint16_t* w_src = p.Wt + ((int64_t)(m0 + st_n) * p.Cp + st_ch * 8);
+    const int64_t w_round = (int64_t)ROWS_PER_ROUND * p.Cp;   // elements between a thread's chunks
+    const int64_t w_next = p.Mp * p.Cp;                       // elements between offsets
+    // (the loads below are issued unconditionally in every iteration, re-reading the last
+    // offset at the end of the loop: with a fixed number of loads per iteration the compiler's
+    // wait counts let the previous iteration's loads be consumed while these are in flight)
+    auto stage_load = [&](u32x4 (&reg)[PER_THREAD], bool advance) {
+#pragma unroll
+        for (int j = 0; j < PER_THREAD; ++j) reg[j] = *reinterpret_cast<const u32x4*>(w_src + j * w_round);
+        w_src += advance ? w_next : 0;
+    };
+    auto stage_store = [&](int buf, const u32x4 (&reg)[PER_THREAD]) {
+#pragma unroll
+        for (int j = 0; j < PER_THREAD; ++j) {
+            const int n = st_n + ROWS_PER_ROUND * j;
+            *reinterpret_cast<u32x4*>(&lds[buf][n * ROWB + swizzled_chunk<CH>(n, st_ch) * 16]) = reg[j];
+        }
+    };
+    // A fragments: k-step ks needs channels 16 ks + 8 (lane / 32) + [0, 8) of the lane's row.
+    // Every lane always loads (no divergent or data-dependent branch between the loads, so the
+    // compiler can count exactly how many are in flight): a lane without an input point reads
+    // row 0, which is harmless because its result rows are later multiplied by a zero value;
+    // a k-step past C (weights are zero there) re-reads the last real one; when the last real
+    // k-step holds 8 channels, both lane halves read those.  32-bit element offsets from In.
+    const uint32_t full_h = (uint32_t)half * 8u, tail_h = odd ? 0u : full_h;
+    auto gather = [&](int32_t y, i16x8 (&a)[KS]) {
+        const uint32_t row = (uint32_t)max(y, 0) * (uint32_t)p.ld_in;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int kk = min(ks, ksteps - 1);   // uniform
+            const uint32_t off = row + (uint32_t)kk * 16u + (kk == ksteps - 1 ? tail_h : full_h);
+            a[ks] = __builtin_bit_cast(i16x8, *reinterpret_cast<const u32x4*>(In + (uint64_t)off));
+        }
+    };
+    auto table = [&](int32_t& y, uint16_t& vbits, bool advance) {
+        y = *tab_y;
+        vbits = *tab_v;   // unspecified where y < 0
+        tab_y += advance ? p.Xp : 0;
+        tab_v += advance ? p.Xp : 0;
+    };
+
+    f32x16 total[NT];
+#pragma unroll
+    for (int ni = 0; ni < NT; ++ni)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) total[ni][r] = 0.f;
+
+    u32x4 wreg[PER_THREAD];
+    i16x8 a[KS], a_next[KS];
+    int32_t y0 = -1, y1 = -1, y2 = -1;
+    uint16_t v0 = 0, v1 = 0, v2 = 0;   // value bits; converted where they are used
+    // Z >= 1 here
+    stage_load(wreg, p.Z > 1);
+    table(y0, v0, p.Z > 1);
+    table(y1, v1, p.Z > 2);
+    gather(y0, a);
+    stage_store(0, wreg);
+    __syncthreads();
+
+    // byte offset of this lane's B fragment for k-step 0, column block 0, inside a buffer
+    const int b_row = l32 * ROWB;
+
+    for (int64_t z = 0; z < p.Z; ++z) {
+        const int buf = (int)(z & 1);
+        stage_load(wreg, z + 2 < p.Z);   // offset min(z + 1, Z - 1)
+        gather(y1, a_next);
+        table(y2, v2, z + 3 < p.Z);      // offset min(z + 2, Z - 1)
+
+        if (__ballot(y0 >= 0) != 0) {   // some output point of this wavefront has offset z
+            f32x16 acc[NT];
+#pragma unroll
+            for (int ni = 0; ni < NT; ++ni)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[ni][r] = 0.f;
+            // every k-step up to 16 KS runs: weights past C are zero in LDS
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const int pos = swizzled_chunk<CH>(l32, ks * 2 + half) * 16;   // 32 | ni * 32: same swizzle
+#pragma unroll
+                for (int ni = 0; ni < NT; ++ni) {
+                    const i16x8 b = *reinterpret_cast<const i16x8*>(&lds[buf][ni * 32 * ROWB + b_row + pos]);
+                    acc[ni] = mfma32<T>(a[ks], b, acc[ni]);
+                }
+            }
+            const float v_row = y0 >= 0 ? half_bits_to_float(v0, T{}) : 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float vr = __shfl(v_row, 8 * (r / 4) + 4 * half + (r % 4));
+#pragma unroll
+                for (int ni = 0; ni < NT; ++ni) total[ni][r] = fmaf(vr, acc[ni][r], total[ni][r]);
+            }
+        }
+        stage_store(buf ^ 1, wreg);
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) a[ks] = a_next[ks];
+        y0 = y1, v0 = v1, y1 = y2, v1 = v2;
+    }
+
+    // accumulator register r: output point 8 (r / 4) + 4 (lane / 32) + r % 4 of the wavefront's
+    // 32, output channel m0 + 32 ni + lane % 32
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int64_t x = xblk * 128 + wv * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+        if (x < p.X) {
+#pragma unroll
+            for (int ni = 0; ni < NT; ++ni) {
+                const int64_t m = m0 + ni * 32 + l32;
+                if (m < p.M) {
+                    float* out = p.Out + x * p.ld_out + m;
+                    *out = p.accumulate ? *out + total[ni][r] : total[ni][r];
+                }
+            }
+        }
+    }
+}
+
+// Contributions of the slots that lost their table cell: one work-group per slot (strided),
+// one thread per output channel, fp32 atomics.  Runs after spconv_os has stored Out.
+template <typename T>
+__global__ __launch_bounds__(256) void spconv_overflow(ConvParams p, OsParams o) {
+    const int32_t count = *o.ovf_count;
+    const T* In = static_cast<const T*>(p.In);
+    const T* W = static_cast<const T*>(p.W);
+    const T* V = static_cast<const T*>(p.MAPV);
+    for (int32_t e = blockIdx.x; e < count; e += gridDim.x) {
+        const int64_t s = o.ovf[e];
+        const float v = to_float(V[s]);
+        const T* in = In + (int64_t)p.MAPY[s] * p.ld_in;
+        const T* w = W + (int64_t)p.MAPZ[s / p.g] * p.C * p.M;
+        for (int64_t m = threadIdx.x; m < p.M; m += 256) {
+            float acc = 0.f;
+            for (int64_t c = 0; c < p.C; ++c) acc = fmaf(to_float(in[c]), to_float(w[c * p.M + m]), acc);
+            unsafeAtomicAdd(p.Out + (int64_t)p.MAPX[s] * p.ld_out + m, v * acc);
+        }
+    }
+}
+
+struct OsLayout {   // workspace carving for the output-stationary schedule
+    int64_t Xp, Mp;
+    int32_t Cp;
+    size_t off_tabY, off_tabV, off_wt, off_count, off_ovf, bytes;
+};
+
+inline int ks_for(int64_t C) { return C <= 32 ? 2 : C <= 64 ? 4 : C <= 128 ? 8 : 16; }
+
+OsLayout os_layout(int64_t X, int64_t Z, int64_t C, int64_t M, int64_t slots) {
+    OsLayout L;
+    L.Xp = ceil_div(X, 128) * 128;
+    L.Mp = ceil_div(M, 64) * 64;
+    L.Cp = 16 * ks_for(C);
+    size_t b = 256;   // slack for aligning the caller's pointer
+    L.off_tabY = b, b += align_up((size_t)(Z * L.Xp) * 4, 256);
+    L.off_tabV = b, b += align_up((size_t)(Z * L.Xp) * 2, 256);
+    L.off_wt = b, b += align_up((size_t)(Z * L.Mp * L.Cp) * 2, 256);
+    L.off_count = b, b += 256;
+    L.off_ovf = b, b += align_up((size_t)std::max<int64_t>(slots, 1) * 4, 256);
+    L.bytes = b;
+    return L;
+}
+
+// The schedule pays off when an offset reaches a few of every 32 output points; below that
+// most of its passes would be empty and the scatter kernel is used.
+bool os_shape_ok(int64_t X, int64_t Z, int64_t C, int64_t M, int64_t slots, insum_dtype dt) {
+    // (row offsets into In are 32-bit element counts: checked by the caller, which knows Y and ld_in)
+    return dt != INSUM_F32 && C % 8 == 0 && C >= 8 && C <= 256 && X > 0 && Z > 0 && M > 0 &&
+           slots * 16 >= X * Z && slots < (1LL << 31) && Z * (ceil_div(X, 128) * 128) < (1LL << 40) &&
+           ceil_div(X, 128) * ceil_div(M, 64) + 8 * ceil_div(M, 64) < (1LL << 31);
+}
+
+template <typename T>
+void launch_os(const ConvParams& p, OsParams o, hipStream_t s) {
+    hipLaunchKernelGGL(table_fill, dim3((unsigned)ceil_div(o.Z * o.Xp, 256)), dim3(256), 0, s, o.tabY,
+                       o.Z * o.Xp, o.ovf_count);
+    hipLaunchKernelGGL(table_build, dim3((unsigned)ceil_div(p.slots, 256)), dim3(256), 0, s, p, o);
+    hipLaunchKernelGGL(weight_transpose, dim3((unsigned)ceil_div(o.Z * o.Mp * o.Cp, 256)), dim3(256), 0, s,
+                       static_cast<const uint16_t*>(p.W), o);
+    const unsigned grid = (unsigned)(ceil_div(o.x_blocks, 8) * 8 * o.m_tiles);
+    switch (o.Cp / 16) {
+        case 2: hipLaunchKernelGGL((spconv_os<T, 2>), dim3(grid), dim3(256), 0, s, o); break;
+        case 4: hipLaunchKernelGGL((spconv_os<T, 4>), dim3(grid), dim3(256), 0, s, o); break;
+        case 8: hipLaunchKernelGGL((spconv_os<T, 8>), dim3(grid), dim3(256), 0, s, o); break;
+        default: hipLaunchKernelGGL((spconv_os<T, 16>), dim3(grid), dim3(256), 0, s, o); break;
+    }
+    hipLaunchKernelGGL(spconv_overflow<T>, dim3(256), dim3(256), 0, s, p, o);
+}
+
 template <typename T, int KS, int NT>
 void launch_mfma(ConvParams p, hipStream_t s) {
     const int64_t m_tiles = ceil_div(p.M, 32 * NT);
@@ -296,11 +586,20 @@ void launch_typed(const ConvParams& p, bool mfma_ok, hipStream_t s) {
 
 using namespace insum;
 
+extern "C" size_t insum_spconv_groupcoo_workspace_bytes(int64_t X, int64_t Z, int64_t C, int64_t M,
+                                                        int64_t G, int32_t g, insum_dtype dt) {
+    if (X < 0 || Z < 0 || C < 0 || M < 0 || G < 0 || g <= 0 || !dtype_valid(dt)) return 0;
+    const int64_t slots = G * (int64_t)g;
+    if (!os_shape_ok(X, Z, C, M, slots, dt)) return 0;
+    return os_layout(X, Z, C, M, slots).bytes;
+}
+
 extern "C" insum_status insum_spconv_groupcoo(int64_t X, int64_t Y, int64_t Z, int64_t C, int64_t M,
                                               int64_t G, int32_t g, const int32_t* MAPZ,
                                               const int32_t* MAPX, const int32_t* MAPY, const void* MAPV,
                                               const void* In, int64_t ld_in, const void* W, insum_dtype dt,
-                                              float* Out, int64_t ld_out, int accumulate, void* stream) {
+                                              float* Out, int64_t ld_out, int accumulate, void* workspace,
+                                              size_t workspace_bytes, void* stream) {
     if (X < 0 || Y < 0 || Z < 0 || C < 0 || M < 0 || G < 0 || g <= 0) return INSUM_ERR_INVALID_ARG;
     if (X >= (1LL << 31) || Y >= (1LL << 31) || Z >= (1LL << 31) || C >= (1LL << 31) || M >= (1LL << 31))
         return INSUM_ERR_INVALID_ARG;
@@ -312,21 +611,43 @@ extern "C" insum_status insum_spconv_groupcoo(int64_t X, int64_t Y, int64_t Z, i
     if (G > 0 && (X == 0 || Y == 0 || Z == 0)) return INSUM_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (X == 0 || M == 0) return INSUM_OK;
+
+    ConvParams p;
+    p.X = X, p.Y = Y, p.C = C, p.M = M;
+    p.slots = G * (int64_t)g;
+    p.g = g;
+    p.MAPZ = MAPZ, p.MAPX = MAPX, p.MAPY = MAPY, p.MAPV = MAPV;
+    p.In = In, p.ld_in = ld_in, p.W = W, p.Out = Out, p.ld_out = ld_out;
+    p.tiles = ceil_div(p.slots, 32);
+    p.waves_total = 0;
+    const bool rows_ok = ld_in % 8 == 0 && reinterpret_cast<uintptr_t>(In) % 16 == 0;
+
+    if (G > 0 && rows_ok && Y * ld_in < (1LL << 32) && os_shape_ok(X, Z, C, M, p.slots, dt)) {
+        const OsLayout L = os_layout(X, Z, C, M, p.slots);
+        if (!workspace || workspace_bytes < L.bytes) return INSUM_ERR_CAPACITY;
+        char* base = reinterpret_cast<char*>((reinterpret_cast<uintptr_t>(workspace) + 255) / 256 * 256) - 256;
+        OsParams o;
+        o.X = X, o.Z = Z, o.C = C, o.M = M, o.Xp = L.Xp, o.Mp = L.Mp, o.Cp = L.Cp;
+        o.tabY = reinterpret_cast<int32_t*>(base + L.off_tabY);
+        o.tabV = reinterpret_cast<uint16_t*>(base + L.off_tabV);
+        o.Wt = reinterpret_cast<uint16_t*>(base + L.off_wt);
+        o.ovf_count = reinterpret_cast<int32_t*>(base + L.off_count);
+        o.ovf = reinterpret_cast<int32_t*>(base + L.off_ovf);
+        o.In = In, o.ld_in = ld_in, o.Out = Out, o.ld_out = ld_out, o.accumulate = accumulate ? 1 : 0;
+        o.m_tiles = (int32_t)ceil_div(M, 64);
+        o.x_blocks = (int32_t)ceil_div(X, 128);
+        if (dt == INSUM_F16) launch_os<__half>(p, o, s);
+        else launch_os<bf16_t>(p, o, s);
+        INSUM_HIP_TRY(hipGetLastError());
+        return INSUM_OK;
+    }
+
     if (!accumulate) {
         const int64_t n = X * M;
         hipLaunchKernelGGL(fill_zero_rows, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, Out, X, M, ld_out);
     }
     if (G > 0 && C > 0) {
-        ConvParams p;
-        p.X = X, p.Y = Y, p.C = C, p.M = M;
-        p.slots = G * (int64_t)g;
-        p.g = g;
-        p.MAPZ = MAPZ, p.MAPX = MAPX, p.MAPY = MAPY, p.MAPV = MAPV;
-        p.In = In, p.ld_in = ld_in, p.W = W, p.Out = Out, p.ld_out = ld_out;
-        p.tiles = ceil_div(p.slots, 32);
-        p.waves_total = 0;
-        const bool mfma_ok = dt != INSUM_F32 && C % 8 == 0 && C >= 8 && C <= 256 && ld_in % 8 == 0 &&
-                             reinterpret_cast<uintptr_t>(In) % 16 == 0 &&
+        const bool mfma_ok = dt != INSUM_F32 && C % 8 == 0 && C >= 8 && C <= 256 && rows_ok &&
                              ceil_div(M, 64) < 65536 && ceil_div(p.slots, kSlotsPerBlock) < (1LL << 31);
         if (ceil_div(M, 256) >= 65536 || ceil_div(p.slots, kSlotsPerBlock) >= (1LL << 31))
             return INSUM_ERR_UNSUPPORTED;

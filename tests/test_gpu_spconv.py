@@ -204,17 +204,22 @@ def test_spconv_argument_errors():
     W = values_to_torch(_features(16, 16, 0, "f16", lead=27), "f16")
     from paper_2510_17505_amd import api
     Out = torch.empty((P, 16), dtype=torch.float32, device="cuda")
+    need = I.insum_spconv_groupcoo_workspace_bytes(Map, 16, 16, torch.float16)
+    assert need > 0
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
 
     def call(**kw):
         a = dict(X=P, Y=P, Z=27, C=16, M=16, G=Map.G, g=Map.g, MAPZ=Map.MAPZ.data_ptr(), MAPX=Map.MAPX.data_ptr(),
                  MAPY=Map.MAPY.data_ptr(), MAPV=Map.MAPV.data_ptr(), In=In.data_ptr(), ld_in=16,
-                 W=W.data_ptr(), dt=1, Out=Out.data_ptr(), ld_out=16, acc=0, stream=0)
+                 W=W.data_ptr(), dt=1, Out=Out.data_ptr(), ld_out=16, acc=0, ws=ws.data_ptr(), ws_bytes=ws.numel(),
+                 stream=0)
         a.update(kw)
         return api._conv(*a.values())
 
     assert call() == 0
     assert call(g=0) == 1 and call(ld_in=8) == 1 and call(ld_out=8) == 1 and call(dt=7) == 1
     assert call(MAPZ=0) == 1 and call(In=0) == 1 and call(Out=0) == 1 and call(C=-1) == 1
+    assert call(ws_bytes=need - 1) == 4 and call(ws=0) == 4          # workspace too small / missing
     torch.cuda.synchronize()
 
 
