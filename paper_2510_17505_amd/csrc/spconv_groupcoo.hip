@@ -28,6 +28,7 @@
 // Shapes outside the MFMA conditions and fp32 inputs run spconv_general: one thread per
 // (slot, m), fp32 FMAs in channel order.
 #include <algorithm>
+#include <type_traits>
 
 #include "common.h"
 
@@ -293,9 +294,11 @@ struct OsParams {
     int32_t* tabY;        // [Z][Xp]
     uint16_t* tabV;       // [Z][Xp]
     uint16_t* Wt;         // [Z][Mp][Cp]
-    int64_t Mp;           // M rounded up to a multiple of 64
+    int64_t Mp;           // M rounded up to a multiple of 128
     int32_t Cp;           // 16 * KS
     int32_t* ovf_count;   // one counter
+    int32_t* nonunit;     // set when some nonzero map value differs from 1
+    uint16_t* zeros;      // 16 * KS zero halves (the "row" of an absent input point)
     int32_t* ovf;         // [slots] slot ids
     const void* In;
     int64_t ld_in;
@@ -305,17 +308,20 @@ struct OsParams {
     int32_t m_tiles, x_blocks;
 };
 
-__global__ void table_fill(int32_t* tabY, int64_t n, int32_t* ovf_count) {
+__global__ void table_fill(OsParams o) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < n) tabY[i] = -1;
-    if (i == 0) *ovf_count = 0;
+    if (i < o.Z * o.Xp) o.tabY[i] = -1;
+    if (i < 256) o.zeros[i] = 0;
+    if (i == 0) *o.ovf_count = 0, *o.nonunit = 0;
 }
 
-__global__ void table_build(ConvParams p, OsParams o) {
+// one_bits: the bit pattern of 1.0 in the map's value type
+__global__ void table_build(ConvParams p, OsParams o, uint16_t one_bits) {
     const int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (s >= p.slots) return;
     const uint16_t vbits = static_cast<const uint16_t*>(p.MAPV)[s];
     if ((vbits & 0x7fffu) == 0) return;  // +-0: padding or an explicit zero, contributes nothing
+    if (vbits != one_bits) *o.nonunit = 1;
     const int64_t cell = (int64_t)p.MAPZ[s / p.g] * o.Xp + p.MAPX[s];
     if (atomicCAS(&o.tabY[cell], -1, p.MAPY[s]) == -1)
         o.tabV[cell] = vbits;
@@ -338,10 +344,17 @@ __device__ inline int swizzled_chunk(int n, int ch) {
     else return ch ^ ((n / (16 / CH)) % CH);
 }
 
-// (KS = 16 needs more than 256 registers for its two sets of A fragments: one wavefront per SIMD)
-template <typename T, int KS>
+// Two variants are launched for every call and one of them returns at once, according to the
+// flag table_build leaves behind (the host never waits for it):
+//   UNIT   every nonzero map value is 1, as in a plain convolution: the k-steps accumulate
+//          straight into the running sums, which leaves registers for NT = 4 column blocks, so
+//          the rows of an offset are gathered once for 128 output channels.  Absent input
+//          points read a row of zeros kept in the workspace.
+//   !UNIT  general values: NT = 2 and a separate accumulator per offset, scaled by the values.
+// (KS = 16 needs more than 256 registers for its sets of A fragments: one wavefront per SIMD)
+template <typename T, int KS, int NT, bool UNIT>
 __global__ __launch_bounds__(256, KS == 16 ? 1 : 2) void spconv_os(OsParams p) {
-    constexpr int NT = 2;                  // column blocks of 32 output channels per work-group
+    if ((*p.nonunit != 0) == UNIT) return;   // the other variant runs
     constexpr int CH = 2 * KS;             // 16-byte chunks per weight row
     constexpr int ROWB = CH * 16;          // bytes per weight row in LDS
     constexpr int TILE_CHUNKS = 32 * NT * CH;
@@ -363,22 +376,29 @@ __global__ __launch_bounds__(256, KS == 16 ? 1 : 2) void spconv_os(OsParams p) {
     const bool odd = p.C % 16 == 8;   // the last k-step holds 8 channels only
     const uint16_t* const In = static_cast<const uint16_t*>(p.In);
 
-    // Table cells of this lane's output point, walked offset by offset.
-    const int32_t* tab_y = p.tabY + (xblk * 128 + wv * 32 + l32);
-    const uint16_t* tab_v = p.tabV + (xblk * 128 + wv * 32 + l32);
+    // Offsets are visited cyclically from a start that differs between work-groups.  All
+    // work-groups march through the offsets at about the same pace; started together they would
+    // all stage the same 16 KB of weights at the same time, from the few L2 channels that hold it.
+    const int Z = (int)p.Z;
+    const int z_start = (int)((xblk * 7 + mt * 3) % Z);
+    auto next_z = [&](int z) { return z + 1 == Z ? 0 : z + 1; };
+
+    // Table cells of this lane's output point.
+    const int32_t* const tab_y = p.tabY + (xblk * 128 + wv * 32 + l32);
+    const uint16_t* const tab_v = p.tabV + (xblk * 128 + wv * 32 + l32);
 
     // Weight staging: thread owns chunk tid % CH of rows tid / CH + ROWS_PER_ROUND j.
     const int st_n = tid / CH, st_ch = tid % CH;
-    const uint16_t* w_src = p.Wt + ((int64_t)(m0 + st_n) * p.Cp + st_ch * 8);
+    const uint16_t* const w_src = p.Wt + ((int64_t)(m0 + st_n) * p.Cp + st_ch * 8);
     const int64_t w_round = (int64_t)ROWS_PER_ROUND * p.Cp;   // elements between a thread's chunks
     const int64_t w_next = p.Mp * p.Cp;                       // elements between offsets
-    // (the loads below are issued unconditionally in every iteration, re-reading the last
-    // offset at the end of the loop: with a fixed number of loads per iteration the compiler's
-    // wait counts let the previous iteration's loads be consumed while these are in flight)
-    auto stage_load = [&](u32x4 (&reg)[PER_THREAD], bool advance) {
+    // (the loads of an iteration are issued unconditionally, wrapping around at the end of the
+    // loop: with a fixed number of loads per iteration the compiler's wait counts let older
+    // loads be consumed while newer ones are in flight)
+    auto stage_load = [&](u32x4 (&reg)[PER_THREAD], int z) {
+        const uint16_t* src = w_src + z * w_next;
 #pragma unroll
-        for (int j = 0; j < PER_THREAD; ++j) reg[j] = *reinterpret_cast<const u32x4*>(w_src + j * w_round);
-        w_src += advance ? w_next : 0;
+        for (int j = 0; j < PER_THREAD; ++j) reg[j] = *reinterpret_cast<const u32x4*>(src + j * w_round);
     };
     auto stage_store = [&](int buf, const u32x4 (&reg)[PER_THREAD]) {
 #pragma unroll
@@ -396,18 +416,19 @@ __global__ __launch_bounds__(256, KS == 16 ? 1 : 2) void spconv_os(OsParams p) {
     const uint32_t full_h = (uint32_t)half * 8u, tail_h = odd ? 0u : full_h;
     auto gather = [&](int32_t y, i16x8 (&a)[KS]) {
         const uint32_t row = (uint32_t)max(y, 0) * (uint32_t)p.ld_in;
+        // UNIT: nothing multiplies an absent point's result rows by zero later, so its rows
+        // must be zero themselves
+        const uint16_t* base = (UNIT && y < 0) ? p.zeros : In + (uint64_t)row;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const int kk = min(ks, ksteps - 1);   // uniform
-            const uint32_t off = row + (uint32_t)kk * 16u + (kk == ksteps - 1 ? tail_h : full_h);
-            a[ks] = __builtin_bit_cast(i16x8, *reinterpret_cast<const u32x4*>(In + (uint64_t)off));
+            const uint32_t off = (uint32_t)kk * 16u + (kk == ksteps - 1 ? tail_h : full_h);
+            a[ks] = __builtin_bit_cast(i16x8, *reinterpret_cast<const u32x4*>(base + off));
         }
     };
-    auto table = [&](int32_t& y, uint16_t& vbits, bool advance) {
-        y = *tab_y;
-        vbits = *tab_v;   // unspecified where y < 0
-        tab_y += advance ? p.Xp : 0;
-        tab_v += advance ? p.Xp : 0;
+    auto table = [&](int32_t& y, uint16_t& vbits, int z) {
+        y = tab_y[z * p.Xp];
+        vbits = tab_v[z * p.Xp];   // unspecified where y < 0
     };
 
     f32x16 total[NT];
@@ -417,55 +438,81 @@ __global__ __launch_bounds__(256, KS == 16 ? 1 : 2) void spconv_os(OsParams p) {
         for (int r = 0; r < 16; ++r) total[ni][r] = 0.f;
 
     u32x4 wreg[PER_THREAD];
-    i16x8 a[KS], a_next[KS];
-    int32_t y0 = -1, y1 = -1, y2 = -1;
-    uint16_t v0 = 0, v1 = 0, v2 = 0;   // value bits; converted where they are used
-    // Z >= 1 here
-    stage_load(wreg, p.Z > 1);
-    table(y0, v0, p.Z > 1);
-    table(y1, v1, p.Z > 2);
+    // Software pipeline: rows are requested two offsets ahead (three sets of A fragments), table
+    // cells three offsets ahead, weights one offset ahead.  Within an iteration the table load
+    // is issued first: the next iteration needs it first, and the load counter is in order.
+    i16x8 a[KS], a1[KS], a2[KS];
+    int32_t y0, y1, y2, y3 = -1;
+    uint16_t v0, v1, v2, v3 = 0;   // value bits; converted where they are used
+    // Z >= 1 here.  zw / zg / zt: the offsets whose weights, rows and table cells are requested next.
+    int zw = z_start, zt = z_start;
+    stage_load(wreg, zw), zw = next_z(zw);
+    table(y0, v0, zt), zt = next_z(zt);
+    table(y1, v1, zt), zt = next_z(zt);
+    table(y2, v2, zt), zt = next_z(zt);
     gather(y0, a);
+    gather(y1, a1);
     stage_store(0, wreg);
     __syncthreads();
 
     // byte offset of this lane's B fragment for k-step 0, column block 0, inside a buffer
     const int b_row = l32 * ROWB;
 
-    for (int64_t z = 0; z < p.Z; ++z) {
-        const int buf = (int)(z & 1);
-        stage_load(wreg, z + 2 < p.Z);   // offset min(z + 1, Z - 1)
-        gather(y1, a_next);
-        table(y2, v2, z + 3 < p.Z);      // offset min(z + 2, Z - 1)
+    // One offset (iteration i): `use` holds its rows, `fill` receives those of iteration i + 2.  The loop below is
+    // unrolled three times so that the three fragment sets rotate by name; a register-to-register
+    // rotation would have to wait for the loads it moves.  Iterations at or past Z (at most two,
+    // when Z is not a multiple of three) run with every point absent.
+    auto one_offset = [&](int i, const i16x8 (&use)[KS], i16x8 (&fill)[KS]) {
+        const int buf = i & 1;
+        table(y3, v3, zt), zt = next_z(zt);      // iteration i + 3
+        stage_load(wreg, zw), zw = next_z(zw);   // iteration i + 1
+        gather(i + 2 < Z ? y2 : -1, fill);       // iteration i + 2 (nothing past the last one)
 
-        if (__ballot(y0 >= 0) != 0) {   // some output point of this wavefront has offset z
-            f32x16 acc[NT];
-#pragma unroll
-            for (int ni = 0; ni < NT; ++ni)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[ni][r] = 0.f;
+        const bool present = i < Z && y0 >= 0;
+        if (__ballot(present) != 0) {   // some output point of this wavefront has offset z
             // every k-step up to 16 KS runs: weights past C are zero in LDS
+            if constexpr (UNIT) {
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const int pos = swizzled_chunk<CH>(l32, ks * 2 + half) * 16;   // 32 | ni * 32: same swizzle
+                for (int ks = 0; ks < KS; ++ks) {
+                    const int pos = swizzled_chunk<CH>(l32, ks * 2 + half) * 16;   // 32 | ni * 32: same swizzle
 #pragma unroll
-                for (int ni = 0; ni < NT; ++ni) {
-                    const i16x8 b = *reinterpret_cast<const i16x8*>(&lds[buf][ni * 32 * ROWB + b_row + pos]);
-                    acc[ni] = mfma32<T>(a[ks], b, acc[ni]);
+                    for (int ni = 0; ni < NT; ++ni) {
+                        const i16x8 b = *reinterpret_cast<const i16x8*>(&lds[buf][ni * 32 * ROWB + b_row + pos]);
+                        total[ni] = mfma32<T>(use[ks], b, total[ni]);
+                    }
                 }
-            }
-            const float v_row = y0 >= 0 ? half_bits_to_float(v0, T{}) : 0.f;
+            } else {
+                f32x16 acc[NT];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float vr = __shfl(v_row, 8 * (r / 4) + 4 * half + (r % 4));
+                for (int ni = 0; ni < NT; ++ni)
 #pragma unroll
-                for (int ni = 0; ni < NT; ++ni) total[ni][r] = fmaf(vr, acc[ni][r], total[ni][r]);
+                    for (int r = 0; r < 16; ++r) acc[ni][r] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const int pos = swizzled_chunk<CH>(l32, ks * 2 + half) * 16;
+#pragma unroll
+                    for (int ni = 0; ni < NT; ++ni) {
+                        const i16x8 b = *reinterpret_cast<const i16x8*>(&lds[buf][ni * 32 * ROWB + b_row + pos]);
+                        acc[ni] = mfma32<T>(use[ks], b, acc[ni]);
+                    }
+                }
+                const float v_row = present ? half_bits_to_float(v0, T{}) : 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float vr = __shfl(v_row, 8 * (r / 4) + 4 * half + (r % 4));
+#pragma unroll
+                    for (int ni = 0; ni < NT; ++ni) total[ni][r] = fmaf(vr, acc[ni][r], total[ni][r]);
+                }
             }
         }
         stage_store(buf ^ 1, wreg);
         __syncthreads();
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) a[ks] = a_next[ks];
-        y0 = y1, v0 = v1, y1 = y2, v1 = v2;
+        y0 = y1, v0 = v1, y1 = y2, v1 = v2, y2 = y3, v2 = v3;
+    };
+    for (int i = 0; i < Z; i += 3) {
+        one_offset(i, a, a2);
+        one_offset(i + 1, a1, a);
+        one_offset(i + 2, a2, a1);
     }
 
     // accumulator register r: output point 8 (r / 4) + 4 (lane / 32) + r % 4 of the wavefront's
@@ -510,7 +557,7 @@ __global__ __launch_bounds__(256) void spconv_overflow(ConvParams p, OsParams o)
 struct OsLayout {   // workspace carving for the output-stationary schedule
     int64_t Xp, Mp;
     int32_t Cp;
-    size_t off_tabY, off_tabV, off_wt, off_count, off_ovf, bytes;
+    size_t off_tabY, off_tabV, off_wt, off_count, off_zeros, off_ovf, bytes;
 };
 
 inline int ks_for(int64_t C) { return C <= 32 ? 2 : C <= 64 ? 4 : C <= 128 ? 8 : 16; }
@@ -518,13 +565,14 @@ inline int ks_for(int64_t C) { return C <= 32 ? 2 : C <= 64 ? 4 : C <= 128 ? 8 :
 OsLayout os_layout(int64_t X, int64_t Z, int64_t C, int64_t M, int64_t slots) {
     OsLayout L;
     L.Xp = ceil_div(X, 128) * 128;
-    L.Mp = ceil_div(M, 64) * 64;
+    L.Mp = ceil_div(M, 128) * 128;
     L.Cp = 16 * ks_for(C);
     size_t b = 256;   // slack for aligning the caller's pointer
     L.off_tabY = b, b += align_up((size_t)(Z * L.Xp) * 4, 256);
     L.off_tabV = b, b += align_up((size_t)(Z * L.Xp) * 2, 256);
     L.off_wt = b, b += align_up((size_t)(Z * L.Mp * L.Cp) * 2, 256);
-    L.off_count = b, b += 256;
+    L.off_count = b, b += 256;   // overflow counter, non-unit flag
+    L.off_zeros = b, b += 512;
     L.off_ovf = b, b += align_up((size_t)std::max<int64_t>(slots, 1) * 4, 256);
     L.bytes = b;
     return L;
@@ -539,19 +587,32 @@ bool os_shape_ok(int64_t X, int64_t Z, int64_t C, int64_t M, int64_t slots, insu
            ceil_div(X, 128) * ceil_div(M, 64) + 8 * ceil_div(M, 64) < (1LL << 31);
 }
 
+template <typename T, int KS, int NT, bool UNIT>
+void launch_os_variant(OsParams o, hipStream_t s) {
+    o.m_tiles = (int32_t)ceil_div(o.M, 32 * NT);
+    const unsigned grid = (unsigned)(ceil_div(o.x_blocks, 8) * 8 * o.m_tiles);
+    hipLaunchKernelGGL((spconv_os<T, KS, NT, UNIT>), dim3(grid), dim3(256), 0, s, o);
+}
+
+template <typename T, int KS>
+void launch_os_both(const OsParams& o, hipStream_t s) {
+    launch_os_variant<T, KS, (KS == 16 ? 2 : 4), true>(o, s);
+    launch_os_variant<T, KS, 2, false>(o, s);
+}
+
 template <typename T>
-void launch_os(const ConvParams& p, OsParams o, hipStream_t s) {
-    hipLaunchKernelGGL(table_fill, dim3((unsigned)ceil_div(o.Z * o.Xp, 256)), dim3(256), 0, s, o.tabY,
-                       o.Z * o.Xp, o.ovf_count);
-    hipLaunchKernelGGL(table_build, dim3((unsigned)ceil_div(p.slots, 256)), dim3(256), 0, s, p, o);
+void launch_os(const ConvParams& p, const OsParams& o, hipStream_t s) {
+    const uint16_t one_bits = sizeof(T) == 2 && std::is_same<T, __half>::value ? 0x3C00 : 0x3F80;
+    hipLaunchKernelGGL(table_fill, dim3((unsigned)ceil_div(std::max<int64_t>(o.Z * o.Xp, 256), 256)), dim3(256),
+                       0, s, o);
+    hipLaunchKernelGGL(table_build, dim3((unsigned)ceil_div(p.slots, 256)), dim3(256), 0, s, p, o, one_bits);
     hipLaunchKernelGGL(weight_transpose, dim3((unsigned)ceil_div(o.Z * o.Mp * o.Cp, 256)), dim3(256), 0, s,
                        static_cast<const uint16_t*>(p.W), o);
-    const unsigned grid = (unsigned)(ceil_div(o.x_blocks, 8) * 8 * o.m_tiles);
     switch (o.Cp / 16) {
-        case 2: hipLaunchKernelGGL((spconv_os<T, 2>), dim3(grid), dim3(256), 0, s, o); break;
-        case 4: hipLaunchKernelGGL((spconv_os<T, 4>), dim3(grid), dim3(256), 0, s, o); break;
-        case 8: hipLaunchKernelGGL((spconv_os<T, 8>), dim3(grid), dim3(256), 0, s, o); break;
-        default: hipLaunchKernelGGL((spconv_os<T, 16>), dim3(grid), dim3(256), 0, s, o); break;
+        case 2: launch_os_both<T, 2>(o, s); break;
+        case 4: launch_os_both<T, 4>(o, s); break;
+        case 8: launch_os_both<T, 8>(o, s); break;
+        default: launch_os_both<T, 16>(o, s); break;
     }
     hipLaunchKernelGGL(spconv_overflow<T>, dim3(256), dim3(256), 0, s, p, o);
 }
@@ -632,9 +693,11 @@ extern "C" insum_status insum_spconv_groupcoo(int64_t X, int64_t Y, int64_t Z, i
         o.tabV = reinterpret_cast<uint16_t*>(base + L.off_tabV);
         o.Wt = reinterpret_cast<uint16_t*>(base + L.off_wt);
         o.ovf_count = reinterpret_cast<int32_t*>(base + L.off_count);
+        o.nonunit = o.ovf_count + 1;
+        o.zeros = reinterpret_cast<uint16_t*>(base + L.off_zeros);
         o.ovf = reinterpret_cast<int32_t*>(base + L.off_ovf);
         o.In = In, o.ld_in = ld_in, o.Out = Out, o.ld_out = ld_out, o.accumulate = accumulate ? 1 : 0;
-        o.m_tiles = (int32_t)ceil_div(M, 64);
+        o.m_tiles = 0;   // set per variant
         o.x_blocks = (int32_t)ceil_div(X, 128);
         if (dt == INSUM_F16) launch_os<__half>(p, o, s);
         else launch_os<bf16_t>(p, o, s);

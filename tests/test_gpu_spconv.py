@@ -132,14 +132,24 @@ def _run_conv(X, Y, Z, mx, my, mz, mv, C, M, dtype, g, seed=0, ld_in=None, accum
     return got_map
 
 
+@pytest.mark.parametrize("values", ["ones", "normal"])
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 @pytest.mark.parametrize("C,M", [(128, 128), (64, 64), (32, 96), (256, 256), (16, 32), (8, 8), (72, 100),
                                  (256, 40), (128, 160)])
-def test_spconv_voxel_mfma(dtype, C, M):
+def test_spconv_voxel_mfma(dtype, C, M, values):
     """Matrix-core path: every instantiation (C up to 32 / 64 / 128 / 256), channel counts that
-    end inside a k-step, output widths that end inside a column block or need several m-tiles."""
-    P, mx, my, mz, mv = synth.voxel_kernel_map(14, 0.3, seed=C + M, dtype=dtype, values="normal")
+    end inside a k-step, output widths that end inside a column block or need several m-tiles;
+    map values all one (a plain convolution, its own kernel variant) and general."""
+    P, mx, my, mz, mv = synth.voxel_kernel_map(14, 0.3, seed=C + M, dtype=dtype, values=values)
     _run_conv(P, P, 27, mx, my, mz, mv, C, M, dtype, None, seed=C)
+
+
+def test_spconv_one_value_differs_from_one():
+    """A single map value other than 1 switches the whole call to the general variant."""
+    P, mx, my, mz, mv = synth.voxel_kernel_map(14, 0.3, seed=5, dtype="f16")
+    mv = mv.copy()
+    mv[mv.size // 2] = -2.5
+    _run_conv(P, P, 27, mx, my, mz, mv, 64, 64, "f16", None, seed=7)
 
 
 @pytest.mark.parametrize("g", [1, 2, 5, 16, 32, 48, 256])
