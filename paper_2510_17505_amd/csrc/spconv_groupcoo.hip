@@ -4,29 +4,32 @@
 //     Out[MAPX[p,q], m] += MAPV[p,q] * sum_c In[MAPY[p,q], c] * Weight[MAPZ[p], c, m]
 //
 // All slots of a group share one weight matrix, so the work is a sequence of small dense
-// products (gathered rows of In) x Weight[z] whose result rows are scattered into Out.  The
-// paper expresses this as a batched matrix multiply followed by a lazily broadcast atomic add;
-// the mapping to gfx950 below is this library's own:
+// products (gathered rows of In) x Weight[z] whose result rows are added into Out.  The paper
+// expresses this as a batched matrix multiply followed by a lazily broadcast atomic add.  This
+// file holds two mappings of it to gfx950, both this library's own, and a general fallback:
 //
-//   * The slot array [G*g] is cut into tiles of 32 consecutive slots; a tile is one
-//     v_mfma_f32_32x32x16 row block.  A wavefront owns a contiguous range of tiles.  The map
-//     is sorted by offset, so a wavefront sees one offset, rarely two.
-//   * Weight-stationary registers: the wavefront keeps Weight[z][:, m-tile] as MFMA B
-//     fragments in VGPRs (C x 128 halves = 128 registers for C = 128) and reloads them only
-//     when the offset changes.  There is no LDS traffic at all.
-//   * A fragments are the gathered rows themselves: lane l loads the 16 bytes
-//     In[y(l % 32)][16 ks + 8 (l / 32) ...] for every k-step, which is exactly the operand
-//     layout of the instruction.  The next tile's rows are requested before the current
-//     tile's MFMAs are issued.
-//   * A tile whose slots belong to more than one offset (possible where one offset's groups
-//     end and the next begin, and for any g that does not divide 32) is processed once per
-//     offset with the other slots masked.
-//   * Results are scaled by MAPV in fp32 and added to Out with hardware fp32 atomics:
-//     32 consecutive floats of one output row per half wavefront.  A zero MAPV (padding)
-//     issues no atomic.
-//
-// Shapes outside the MFMA conditions and fp32 inputs run spconv_general: one thread per
-// (slot, m), fp32 FMAs in channel order.
+//   spconv_os       output-stationary: the grouped map is walked by output point and the sums
+//                   stay in registers (described further down, above OsParams).  Used when
+//                   the map holds at least X*Z/16 slots.
+//   spconv_mfma     slot-major with an atomic scatter, the paper's shape:
+//     * The slot array [G*g] is cut into tiles of 32 consecutive slots; a tile is one
+//       v_mfma_f32_32x32x16 row block.  A wavefront owns a contiguous range of tiles.  The map
+//       is sorted by offset, so a wavefront sees one offset, rarely two.
+//     * Weight-stationary registers: the wavefront keeps Weight[z][:, m-tile] as MFMA B
+//       fragments in VGPRs (C x 128 halves = 128 registers for C = 128) and reloads them only
+//       when the offset changes.  There is no LDS traffic at all.
+//     * A fragments are the gathered rows themselves: lane l loads the 16 bytes
+//       In[y(l % 32)][16 ks + 8 (l / 32) ...] for every k-step, which is exactly the operand
+//       layout of the instruction.  The next tile's rows are requested before the current
+//       tile's MFMAs are issued.
+//     * A tile whose slots belong to more than one offset (possible where one offset's groups
+//       end and the next begin, and for any g that does not divide 32) is processed once per
+//       offset with the other slots masked.
+//     * Results are scaled by MAPV in fp32 and added to Out with hardware fp32 atomics:
+//       32 consecutive floats of one output row per half wavefront.  A zero MAPV (padding)
+//       issues no atomic.
+//   spconv_general  one thread per (slot, m), fp32 FMAs in channel order, atomics: fp32 inputs
+//                   and shapes outside the MFMA conditions.
 #include <algorithm>
 #include <type_traits>
 
@@ -409,21 +412,26 @@ __global__ __launch_bounds__(256, KS == 16 ? 1 : 2) void spconv_os(OsParams p) {
     };
     // A fragments: k-step ks needs channels 16 ks + 8 (lane / 32) + [0, 8) of the lane's row.
     // Every lane always loads (no divergent or data-dependent branch between the loads, so the
-    // compiler can count exactly how many are in flight): a lane without an input point reads
-    // row 0, which is harmless because its result rows are later multiplied by a zero value;
-    // a k-step past C (weights are zero there) re-reads the last real one; when the last real
-    // k-step holds 8 channels, both lane halves read those.  32-bit element offsets from In.
+    // compiler can count exactly how many are in flight).  A lane without an input point reads
+    // the row of another lane of its quad (the texture addresser works through a load one
+    // 64-byte piece per lane quad at a time, so this costs nothing extra), or row 0 when the
+    // whole quad is absent; what it loaded is then replaced by zeros (UNIT) or multiplied by a
+    // zero value later (!UNIT).  A k-step past C (weights are zero there) re-reads the last real
+    // one; when the last real k-step holds 8 channels, both lane halves read those.
     const uint32_t full_h = (uint32_t)half * 8u, tail_h = odd ? 0u : full_h;
     auto gather = [&](int32_t y, i16x8 (&a)[KS]) {
-        const uint32_t row = (uint32_t)max(y, 0) * (uint32_t)p.ld_in;
-        // UNIT: nothing multiplies an absent point's result rows by zero later, so its rows
-        // must be zero themselves
-        const uint16_t* base = (UNIT && y < 0) ? p.zeros : In + (uint64_t)row;
+        // largest y of the lane's quad: quad_perm [1,0,3,2] then [2,3,0,1]
+        int32_t yq = max(y, __builtin_amdgcn_update_dpp(y, y, 0xB1, 0xF, 0xF, false));
+        yq = max(yq, __builtin_amdgcn_update_dpp(yq, yq, 0x4E, 0xF, 0xF, false));
+        const uint32_t row = (uint32_t)max(y >= 0 ? y : yq, 0) * (uint32_t)p.ld_in;
+        const uint16_t* base = In + (uint64_t)row;
+        const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const int kk = min(ks, ksteps - 1);   // uniform
             const uint32_t off = (uint32_t)kk * 16u + (kk == ksteps - 1 ? tail_h : full_h);
-            a[ks] = __builtin_bit_cast(i16x8, *reinterpret_cast<const u32x4*>(base + off));
+            const u32x4 raw = *reinterpret_cast<const u32x4*>(base + off);
+            a[ks] = __builtin_bit_cast(i16x8, (UNIT && y < 0) ? zero : raw);
         }
     };
     auto table = [&](int32_t& y, uint16_t& vbits, int z) {

@@ -96,3 +96,41 @@ def test_conversion_argument_validation_without_a_gpu():
     assert sb(8, 8, 4, 0, 1, 3, 2, 0, 0, 0, 2, 0, 4, 2, 0, 4, 2, 0, 0, 0, 0) == 5   # M % bM != 0
     assert sb(8, 8, 4, 0, 1, 2, 2, 0, 0, 0, 2, 0, 4, 1, 0, 4, 2, 0, 0, 0, 0) == 5   # dtype mix
     assert sb(8, 8, 4, 0, 1, 2, 2, 0, 0, 0, 2, 0, 4, 2, 0, 4, 2, 0, 0, 0, 0) == 1   # null C
+
+
+def test_sparse_convolution_argument_validation_without_a_gpu():
+    """Kernel-map grouping and the convolution reject malformed calls before touching the device;
+    the workspace size is a pure host function."""
+    I, lib = _lib()
+    i64, i32, p = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p
+    g_used, G = i32(0), i64(0)
+    gu, gg = ctypes.addressof(g_used), ctypes.addressof(G)
+    mconv = lib.insum_map_to_groupcoo
+    mconv.restype = ctypes.c_int
+    mconv.argtypes = [i64, i64, i64, i64, p, p, p, p, ctypes.c_int, i32, p, p, p, p, p, p, i64, p,
+                      ctypes.c_size_t, p]
+    assert mconv(4, 4, 3, -1, 0, 0, 0, 0, 1, 2, gu, gg, 0, 0, 0, 0, 0, 0, 0, 0) == 1    # nnz < 0
+    assert mconv(4, 4, 3, 5, 0, 0, 0, 0, 1, 2, gu, gg, 0, 0, 0, 0, 0, 0, 0, 0) == 1     # null inputs
+    assert mconv(4, 4, 3, 0, 0, 0, 0, 0, 9, 2, gu, gg, 0, 0, 0, 0, 0, 0, 0, 0) == 1     # bad dtype
+    assert mconv(4, 4, 3, 0, 0, 0, 0, 0, 1, 2, gu, 0, 0, 0, 0, 0, 0, 0, 0, 0) == 1      # null out-param
+    assert mconv(4, 4, 3, 0, 0, 0, 0, 0, 1, 0, gu, gg, 0, 0, 0, 0, 0, 0, 0, 0) == 0     # empty map is fine
+    assert g_used.value == 1 and G.value == 0
+    ws = lib.insum_spconv_groupcoo_workspace_bytes
+    ws.restype = ctypes.c_size_t
+    ws.argtypes = [i64, i64, i64, i64, i64, i32, ctypes.c_int]
+    assert ws(1000, 27, 128, 128, 40, 256, 0) == 0            # fp32: scatter kernels, no workspace
+    assert ws(1000, 27, 12, 128, 40, 256, 1) == 0             # C % 8 != 0
+    assert ws(1 << 20, 27, 128, 128, 4, 256, 1) == 0          # far too few slots per output point
+    need = ws(1000, 27, 128, 128, 40, 256, 1)
+    # inverse table (4 + 2 bytes per cell of 27 x 1024), transposed weights, overflow list
+    assert need >= 27 * 1024 * 6 + 27 * 128 * 128 * 2 + 40 * 256 * 4
+    assert ws(1000, 27, 128, 128, 40, 256, 2) == need
+    conv = lib.insum_spconv_groupcoo
+    conv.restype = ctypes.c_int
+    conv.argtypes = [i64, i64, i64, i64, i64, i64, i32, p, p, p, p, p, i64, p, ctypes.c_int, p, i64,
+                     ctypes.c_int, p, ctypes.c_size_t, p]
+    assert conv(8, 8, 3, 16, 16, 0, 0, 0, 0, 0, 0, 0, 16, 0, 1, 0, 16, 0, 0, 0, 0) == 1    # g <= 0
+    assert conv(8, 8, 3, 16, 16, 0, 4, 0, 0, 0, 0, 0, 8, 0, 1, 0, 16, 0, 0, 0, 0) == 1     # ld_in < C
+    assert conv(8, 8, 3, 16, 16, 0, 4, 0, 0, 0, 0, 0, 16, 0, 1, 0, 16, 0, 0, 0, 0) == 1    # null Out
+    assert conv(8, 8, 3, 16, 16, 2, 4, 0, 0, 0, 0, 0, 16, 0, 1, 8, 16, 0, 0, 0, 0) == 1    # null map arrays
+    assert conv(0, 8, 3, 16, 16, 0, 4, 0, 0, 0, 0, 0, 16, 0, 1, 0, 16, 0, 0, 0, 0) == 0    # no output points
