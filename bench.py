@@ -150,6 +150,8 @@ def run_spconv(torch, I, steps, warmup):
     ws = torch.empty(max(1, I.insum_spconv_groupcoo_workspace_bytes(Map, c["C"], c["M"], In.dtype)),
                      dtype=torch.uint8, device="cuda")
     ms = _time_launches(torch, lambda: I.insum_spconv_groupcoo(Map, In, W, Out=Out, workspace=ws), steps, warmup)
+    ms_reuse = _time_launches(torch, lambda: I.insum_spconv_groupcoo(Map, In, W, Out=Out, workspace=ws,
+                                                                     reuse_map_tables=True), steps, warmup)
     S = int(mx.shape[0])
     slots = Map.G * Map.g
     flops = 2.0 * S * c["C"] * c["M"]
@@ -162,6 +164,7 @@ def run_spconv(torch, I, steps, warmup):
     return {"format": "GroupCOO along the kernel offset", "dtype": c["dtype"], "points": P, "nnz": S,
             "C": c["C"], "M": c["M"], "g": Map.g, "groups": Map.G, "ms_per_step": ms, "tflops": tf,
             "executed_tflops": executed / ms / 1e9,
+            "ms_per_step_reusing_map_tables": ms_reuse,   # later layers over the same kernel map
             "model_bytes": int(model_bytes), "model_gbs": model_bytes / ms / 1e6, "conversion_ms": conv_ms,
             "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                          "frac": tf / MFMA_PEAK_TFLOPS, "traffic": _traffic("spconv"),

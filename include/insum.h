@@ -246,6 +246,11 @@ size_t insum_spconv_groupcoo_workspace_bytes(int64_t X, int64_t Z, int64_t C, in
  *   Out         device float[X, ld_out]  output features, M channels per point, fp32
  *   workspace   device scratch, at least insum_spconv_groupcoo_workspace_bytes(...) bytes
  *               (INSUM_ERR_CAPACITY otherwise); may be NULL when that is 0
+ *   reuse_map_tables  0: the call derives its tables from the map.  Nonzero: the caller
+ *               guarantees that `workspace` still holds what an earlier call with the same
+ *               X, Z, C, M, G, g, dt and the same MAPZ/MAPX/MAPY/MAPV contents left there (the
+ *               layers of a network that share one kernel map), so that step is skipped.
+ *               In, W, Out and accumulate may differ between such calls.
  *
  * Products are exact and sums are formed in fp32.  16-bit types with C a multiple of 8, at
  * most 256, ld_in a multiple of 8 and In 16-byte aligned run on the matrix cores, in one of
@@ -261,6 +266,7 @@ insum_status insum_spconv_groupcoo(int64_t X, int64_t Y, int64_t Z, int64_t C, i
                                    const int32_t* MAPZ, const int32_t* MAPX, const int32_t* MAPY,
                                    const void* MAPV, const void* In, int64_t ld_in, const void* W,
                                    insum_dtype dt, float* Out, int64_t ld_out, int accumulate,
+                                   int reuse_map_tables,
                                    void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus

@@ -64,7 +64,7 @@ _conv_ws = _sig("insum_spconv_groupcoo_workspace_bytes", C.c_size_t,
                 [_i64, _i64, _i64, _i64, _i64, _i32, C.c_int])
 _conv = _sig("insum_spconv_groupcoo", C.c_int,
              [_i64, _i64, _i64, _i64, _i64, _i64, _i32, _p, _p, _p, _p, _p, _i64, _p, C.c_int,
-              _p, _i64, C.c_int, _p, C.c_size_t, _p])
+              _p, _i64, C.c_int, C.c_int, _p, C.c_size_t, _p])
 
 
 class InsumError(RuntimeError):
@@ -296,7 +296,7 @@ def insum_spconv_groupcoo_workspace_bytes(Map: MapGroupCOO, C_in: int, M_out: in
 
 def insum_spconv_groupcoo(Map: MapGroupCOO, In: torch.Tensor, W: torch.Tensor,
                           Out: torch.Tensor | None = None, accumulate: bool = False,
-                          workspace=None) -> torch.Tensor:
+                          workspace=None, reuse_map_tables: bool = False) -> torch.Tensor:
     """Out[MAPX[p,q], m] (+)= MAPV[p,q] * In[MAPY[p,q], c] * W[MAPZ[p], c, m]; Out is fp32 [X, M]."""
     assert In.is_cuda and In.dim() == 2 and In.shape[0] == Map.Y and In.stride(1) == 1
     assert W.is_cuda and W.dim() == 3 and W.is_contiguous() and W.shape[0] == Map.Z
@@ -307,10 +307,12 @@ def insum_spconv_groupcoo(Map: MapGroupCOO, In: torch.Tensor, W: torch.Tensor,
     assert Out.dtype == torch.float32
     nws = insum_spconv_groupcoo_workspace_bytes(Map, Cc, M, In.dtype)
     if workspace is None and nws:
+        if reuse_map_tables:
+            raise ValueError("reuse_map_tables=True needs the workspace of the earlier call")
         workspace = torch.empty(nws, dtype=torch.uint8, device=In.device)
     st = _conv(Map.X, Map.Y, Map.Z, Cc, M, Map.G, Map.g, _ptr(Map.MAPZ), _ptr(Map.MAPX), _ptr(Map.MAPY),
                _ptr(Map.MAPV), _ptr(In), In.stride(0), _ptr(W), _DTYPE[In.dtype], _ptr(Out), Out.stride(0),
-               int(bool(accumulate)), _ptr(workspace), 0 if workspace is None else workspace.numel(),
-               _stream())
+               int(bool(accumulate)), int(bool(reuse_map_tables)), _ptr(workspace),
+               0 if workspace is None else workspace.numel(), _stream())
     _check(st, "insum_spconv_groupcoo")
     return Out

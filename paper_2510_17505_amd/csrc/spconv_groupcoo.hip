@@ -301,7 +301,6 @@ struct OsParams {
     int32_t Cp;           // 16 * KS
     int32_t* ovf_count;   // one counter
     int32_t* nonunit;     // set when some nonzero map value differs from 1
-    uint16_t* zeros;      // 16 * KS zero halves (the "row" of an absent input point)
     int32_t* ovf;         // [slots] slot ids
     const void* In;
     int64_t ld_in;
@@ -314,7 +313,6 @@ struct OsParams {
 __global__ void table_fill(OsParams o) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i < o.Z * o.Xp) o.tabY[i] = -1;
-    if (i < 256) o.zeros[i] = 0;
     if (i == 0) *o.ovf_count = 0, *o.nonunit = 0;
 }
 
@@ -351,8 +349,8 @@ __device__ inline int swizzled_chunk(int n, int ch) {
 // flag table_build leaves behind (the host never waits for it):
 //   UNIT   every nonzero map value is 1, as in a plain convolution: the k-steps accumulate
 //          straight into the running sums, which leaves registers for NT = 4 column blocks, so
-//          the rows of an offset are gathered once for 128 output channels.  Absent input
-//          points read a row of zeros kept in the workspace.
+//          the rows of an offset are gathered once for 128 output channels.  The fragments of
+//          absent input points are replaced by zeros before they are used.
 //   !UNIT  general values: NT = 2 and a separate accumulator per offset, scaled by the values.
 // (KS = 16 needs more than 256 registers for its sets of A fragments: one wavefront per SIMD)
 template <typename T, int KS, int NT, bool UNIT>
@@ -565,7 +563,7 @@ __global__ __launch_bounds__(256) void spconv_overflow(ConvParams p, OsParams o)
 struct OsLayout {   // workspace carving for the output-stationary schedule
     int64_t Xp, Mp;
     int32_t Cp;
-    size_t off_tabY, off_tabV, off_wt, off_count, off_zeros, off_ovf, bytes;
+    size_t off_tabY, off_tabV, off_wt, off_count, off_ovf, bytes;
 };
 
 inline int ks_for(int64_t C) { return C <= 32 ? 2 : C <= 64 ? 4 : C <= 128 ? 8 : 16; }
@@ -580,7 +578,6 @@ OsLayout os_layout(int64_t X, int64_t Z, int64_t C, int64_t M, int64_t slots) {
     L.off_tabV = b, b += align_up((size_t)(Z * L.Xp) * 2, 256);
     L.off_wt = b, b += align_up((size_t)(Z * L.Mp * L.Cp) * 2, 256);
     L.off_count = b, b += 256;   // overflow counter, non-unit flag
-    L.off_zeros = b, b += 512;
     L.off_ovf = b, b += align_up((size_t)std::max<int64_t>(slots, 1) * 4, 256);
     L.bytes = b;
     return L;
@@ -609,11 +606,13 @@ void launch_os_both(const OsParams& o, hipStream_t s) {
 }
 
 template <typename T>
-void launch_os(const ConvParams& p, const OsParams& o, hipStream_t s) {
+void launch_os(const ConvParams& p, const OsParams& o, bool reuse_map_tables, hipStream_t s) {
     const uint16_t one_bits = sizeof(T) == 2 && std::is_same<T, __half>::value ? 0x3C00 : 0x3F80;
-    hipLaunchKernelGGL(table_fill, dim3((unsigned)ceil_div(std::max<int64_t>(o.Z * o.Xp, 256), 256)), dim3(256),
-                       0, s, o);
-    hipLaunchKernelGGL(table_build, dim3((unsigned)ceil_div(p.slots, 256)), dim3(256), 0, s, p, o, one_bits);
+    if (!reuse_map_tables) {
+        hipLaunchKernelGGL(table_fill, dim3((unsigned)ceil_div(o.Z * o.Xp, 256)),
+                           dim3(256), 0, s, o);
+        hipLaunchKernelGGL(table_build, dim3((unsigned)ceil_div(p.slots, 256)), dim3(256), 0, s, p, o, one_bits);
+    }
     hipLaunchKernelGGL(weight_transpose, dim3((unsigned)ceil_div(o.Z * o.Mp * o.Cp, 256)), dim3(256), 0, s,
                        static_cast<const uint16_t*>(p.W), o);
     switch (o.Cp / 16) {
@@ -667,7 +666,8 @@ extern "C" insum_status insum_spconv_groupcoo(int64_t X, int64_t Y, int64_t Z, i
                                               int64_t G, int32_t g, const int32_t* MAPZ,
                                               const int32_t* MAPX, const int32_t* MAPY, const void* MAPV,
                                               const void* In, int64_t ld_in, const void* W, insum_dtype dt,
-                                              float* Out, int64_t ld_out, int accumulate, void* workspace,
+                                              float* Out, int64_t ld_out, int accumulate,
+                                              int reuse_map_tables, void* workspace,
                                               size_t workspace_bytes, void* stream) {
     if (X < 0 || Y < 0 || Z < 0 || C < 0 || M < 0 || G < 0 || g <= 0) return INSUM_ERR_INVALID_ARG;
     if (X >= (1LL << 31) || Y >= (1LL << 31) || Z >= (1LL << 31) || C >= (1LL << 31) || M >= (1LL << 31))
@@ -702,13 +702,12 @@ extern "C" insum_status insum_spconv_groupcoo(int64_t X, int64_t Y, int64_t Z, i
         o.Wt = reinterpret_cast<uint16_t*>(base + L.off_wt);
         o.ovf_count = reinterpret_cast<int32_t*>(base + L.off_count);
         o.nonunit = o.ovf_count + 1;
-        o.zeros = reinterpret_cast<uint16_t*>(base + L.off_zeros);
         o.ovf = reinterpret_cast<int32_t*>(base + L.off_ovf);
         o.In = In, o.ld_in = ld_in, o.Out = Out, o.ld_out = ld_out, o.accumulate = accumulate ? 1 : 0;
         o.m_tiles = 0;   // set per variant
         o.x_blocks = (int32_t)ceil_div(X, 128);
-        if (dt == INSUM_F16) launch_os<__half>(p, o, s);
-        else launch_os<bf16_t>(p, o, s);
+        if (dt == INSUM_F16) launch_os<__half>(p, o, reuse_map_tables != 0, s);
+        else launch_os<bf16_t>(p, o, reuse_map_tables != 0, s);
         INSUM_HIP_TRY(hipGetLastError());
         return INSUM_OK;
     }

@@ -221,7 +221,8 @@ def test_spconv_argument_errors():
     def call(**kw):
         a = dict(X=P, Y=P, Z=27, C=16, M=16, G=Map.G, g=Map.g, MAPZ=Map.MAPZ.data_ptr(), MAPX=Map.MAPX.data_ptr(),
                  MAPY=Map.MAPY.data_ptr(), MAPV=Map.MAPV.data_ptr(), In=In.data_ptr(), ld_in=16,
-                 W=W.data_ptr(), dt=1, Out=Out.data_ptr(), ld_out=16, acc=0, ws=ws.data_ptr(), ws_bytes=ws.numel(),
+                 W=W.data_ptr(), dt=1, Out=Out.data_ptr(), ld_out=16, acc=0, reuse=0, ws=ws.data_ptr(),
+                 ws_bytes=ws.numel(),
                  stream=0)
         a.update(kw)
         return api._conv(*a.values())
@@ -263,3 +264,24 @@ def test_spconv_full_size_properties_and_samples():
         abssum += np.abs(In64[my[s]]).sum(axis=0) @ np.abs(W64[z])
     err = np.abs(got.astype(np.float64).sum(axis=0) - colsum)
     assert np.all(err <= 1e-5 * abssum), float((err / abssum).max())
+
+
+@pytest.mark.parametrize("values", ["ones", "normal"])
+def test_spconv_reuses_the_map_tables_across_layers(values):
+    """Two layers over one kernel map: the second call skips the table build and must still
+    match the oracle, with other features, weights and widths of the same tile class."""
+    P, mx, my, mz, mv = synth.voxel_kernel_map(13, 0.3, seed=11, dtype="f16", values=values)
+    st = synth.storage_array(mv, "f16")
+    _, MZ, MX, MY, MV = oracle.map_to_groupcoo(P, P, 27, mx, my, mz, st, None)
+    Map = I.insum_map_to_groupcoo(P, P, 27, _i32(mx), _i32(my), _i32(mz), storage_to_torch(st, "f16"))
+    C, M = 64, 96
+    ws = torch.empty(I.insum_spconv_groupcoo_workspace_bytes(Map, C, M, torch.float16), dtype=torch.uint8,
+                     device="cuda")
+    for layer, reuse in ((0, False), (1, True), (2, True)):
+        In = _features(P, C, 20 + layer, "f16")
+        W = _features(C, M, 30 + layer, "f16", lead=27)
+        got = I.insum_spconv_groupcoo(Map, values_to_torch(In, "f16"), values_to_torch(W, "f16"),
+                                      workspace=ws, reuse_map_tables=reuse)
+        want = oracle.spconv_groupcoo(P, C, M, MZ, MX, MY, MV.astype(np.float32), In, W)
+        absprod = oracle.spconv_groupcoo(P, C, M, MZ, MX, MY, np.abs(MV.astype(np.float32)), np.abs(In), np.abs(W))
+        assert_spmm_close(got.cpu().numpy(), want, absprod, RTOL, f"layer {layer}")

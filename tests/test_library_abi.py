@@ -128,9 +128,9 @@ def test_sparse_convolution_argument_validation_without_a_gpu():
     conv = lib.insum_spconv_groupcoo
     conv.restype = ctypes.c_int
     conv.argtypes = [i64, i64, i64, i64, i64, i64, i32, p, p, p, p, p, i64, p, ctypes.c_int, p, i64,
-                     ctypes.c_int, p, ctypes.c_size_t, p]
-    assert conv(8, 8, 3, 16, 16, 0, 0, 0, 0, 0, 0, 0, 16, 0, 1, 0, 16, 0, 0, 0, 0) == 1    # g <= 0
-    assert conv(8, 8, 3, 16, 16, 0, 4, 0, 0, 0, 0, 0, 8, 0, 1, 0, 16, 0, 0, 0, 0) == 1     # ld_in < C
-    assert conv(8, 8, 3, 16, 16, 0, 4, 0, 0, 0, 0, 0, 16, 0, 1, 0, 16, 0, 0, 0, 0) == 1    # null Out
-    assert conv(8, 8, 3, 16, 16, 2, 4, 0, 0, 0, 0, 0, 16, 0, 1, 8, 16, 0, 0, 0, 0) == 1    # null map arrays
-    assert conv(0, 8, 3, 16, 16, 0, 4, 0, 0, 0, 0, 0, 16, 0, 1, 0, 16, 0, 0, 0, 0) == 0    # no output points
+                     ctypes.c_int, ctypes.c_int, p, ctypes.c_size_t, p]
+    assert conv(8, 8, 3, 16, 16, 0, 0, 0, 0, 0, 0, 0, 16, 0, 1, 0, 16, 0, 0, 0, 0, 0) == 1    # g <= 0
+    assert conv(8, 8, 3, 16, 16, 0, 4, 0, 0, 0, 0, 0, 8, 0, 1, 0, 16, 0, 0, 0, 0, 0) == 1     # ld_in < C
+    assert conv(8, 8, 3, 16, 16, 0, 4, 0, 0, 0, 0, 0, 16, 0, 1, 0, 16, 0, 0, 0, 0, 0) == 1    # null Out
+    assert conv(8, 8, 3, 16, 16, 2, 4, 0, 0, 0, 0, 0, 16, 0, 1, 8, 16, 0, 0, 0, 0, 0) == 1    # null map arrays
+    assert conv(0, 8, 3, 16, 16, 0, 4, 0, 0, 0, 0, 0, 16, 0, 1, 0, 16, 0, 0, 0, 0, 0) == 0    # no output points
