@@ -588,7 +588,8 @@ OsLayout os_layout(int64_t X, int64_t Z, int64_t C, int64_t M, int64_t slots) {
 bool os_shape_ok(int64_t X, int64_t Z, int64_t C, int64_t M, int64_t slots, insum_dtype dt) {
     // (row offsets into In are 32-bit element counts: checked by the caller, which knows Y and ld_in)
     return dt != INSUM_F32 && C % 8 == 0 && C >= 8 && C <= 256 && X > 0 && Z > 0 && M > 0 &&
-           slots * 16 >= X * Z && slots < (1LL << 31) && Z * (ceil_div(X, 128) * 128) < (1LL << 40) &&
+           slots * 16 >= X * Z && slots < (1LL << 31) && Z * (ceil_div(X, 128) * 128) < (1LL << 38) &&
+           Z * (ceil_div(M, 128) * 128) * 256 < (1LL << 38) &&
            ceil_div(X, 128) * ceil_div(M, 64) + 8 * ceil_div(M, 64) < (1LL << 31);
 }
 
@@ -714,6 +715,7 @@ extern "C" insum_status insum_spconv_groupcoo(int64_t X, int64_t Y, int64_t Z, i
 
     if (!accumulate) {
         const int64_t n = X * M;
+        if (ceil_div(n, 256) >= (1LL << 31)) return INSUM_ERR_UNSUPPORTED;
         hipLaunchKernelGGL(fill_zero_rows, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, Out, X, M, ld_out);
     }
     if (G > 0 && C > 0) {

@@ -407,6 +407,7 @@ extern "C" insum_status insum_spmm_groupcoo(int64_t M, int64_t K, int64_t N, int
 
     if (G == 0) {
         if (!accumulate) {
+            if (ceil_div(M * N, 256) >= (1LL << 31)) return INSUM_ERR_UNSUPPORTED;
             const unsigned blocks = (unsigned)ceil_div(M * N, 256);
             if (c_dt == INSUM_F32) hipLaunchKernelGGL(fill_zero_2d<float>, dim3(blocks), dim3(256), 0, s, (float*)C, ldc, M, N);
             else hipLaunchKernelGGL(fill_zero_2d<uint16_t>, dim3(blocks), dim3(256), 0, s, (uint16_t*)C, ldc, M, N);

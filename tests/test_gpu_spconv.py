@@ -285,3 +285,36 @@ def test_spconv_reuses_the_map_tables_across_layers(values):
         want = oracle.spconv_groupcoo(P, C, M, MZ, MX, MY, MV.astype(np.float32), In, W)
         absprod = oracle.spconv_groupcoo(P, C, M, MZ, MX, MY, np.abs(MV.astype(np.float32)), np.abs(In), np.abs(W))
         assert_spmm_close(got.cpu().numpy(), want, absprod, RTOL, f"layer {layer}")
+
+
+def test_spconv_call_can_be_captured_in_a_hip_graph():
+    """The convolution neither allocates nor synchronises nor clears memory with a memset node.
+    On a map without repeated (x, z) pairs the output-stationary schedule uses no atomics, so
+    every replay (with stale workspace contents and eager work in between) must reproduce the
+    eager result bit for bit."""
+    P, mx, my, mz, mv = synth.voxel_kernel_map(16, 0.3, seed=21, dtype="f16")
+    Map = I.insum_map_to_groupcoo(P, P, 27, _i32(mx), _i32(my), _i32(mz), values_to_torch(mv, "f16"))
+    In = values_to_torch(_features(P, 64, 1, "f16"), "f16")
+    W = values_to_torch(_features(64, 128, 2, "f16", lead=27), "f16")
+    need = I.insum_spconv_groupcoo_workspace_bytes(Map, 64, 128, torch.float16)
+    assert need > 0
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    ref = I.insum_spconv_groupcoo(Map, In, W, workspace=ws).clone()
+    Out = torch.empty_like(ref)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            I.insum_spconv_groupcoo(Map, In, W, Out=Out, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(4):
+        Out.fill_(float("nan"))
+        ws.random_(0, 255)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Out, ref), f"replay {rep} differs"
+        _ = I.insum_spconv_groupcoo(Map, In, W, workspace=ws)
+        torch.cuda.synchronize()
