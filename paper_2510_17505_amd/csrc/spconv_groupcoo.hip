@@ -398,10 +398,12 @@ __global__ __launch_bounds__(64 * WV, KS == 16 ? 1 : 2) void spconv_os(OsParams 
     // (the loads of an iteration are issued unconditionally, wrapping around at the end of the
     // loop: with a fixed number of loads per iteration the compiler's wait counts let older
     // loads be consumed while newer ones are in flight)
+    auto stage_load_one = [&](u32x4 (&reg)[PER_THREAD], int z, int j) {
+        reg[j] = *reinterpret_cast<const u32x4*>(w_src + z * w_next + j * w_round);
+    };
     auto stage_load = [&](u32x4 (&reg)[PER_THREAD], int z) {
-        const uint16_t* src = w_src + z * w_next;
 #pragma unroll
-        for (int j = 0; j < PER_THREAD; ++j) reg[j] = *reinterpret_cast<const u32x4*>(src + j * w_round);
+        for (int j = 0; j < PER_THREAD; ++j) stage_load_one(reg, z, j);
     };
     auto stage_store = [&](int buf, const u32x4 (&reg)[PER_THREAD]) {
 #pragma unroll
@@ -419,20 +421,23 @@ __global__ __launch_bounds__(64 * WV, KS == 16 ? 1 : 2) void spconv_os(OsParams 
     // zero value later (!UNIT).  A k-step past C (weights are zero there) re-reads the last real
     // one; when the last real k-step holds 8 channels, both lane halves read those.
     const uint32_t full_h = (uint32_t)half * 8u, tail_h = odd ? 0u : full_h;
-    auto gather = [&](int32_t y, i16x8 (&a)[KS]) {
+    auto gather_row = [&](int32_t y) {   // element offset of the row this lane loads from
         // largest y of the lane's quad: quad_perm [1,0,3,2] then [2,3,0,1]
         int32_t yq = max(y, __builtin_amdgcn_update_dpp(y, y, 0xB1, 0xF, 0xF, false));
         yq = max(yq, __builtin_amdgcn_update_dpp(yq, yq, 0x4E, 0xF, 0xF, false));
-        const uint32_t row = (uint32_t)max(y >= 0 ? y : yq, 0) * (uint32_t)p.ld_in;
-        const uint16_t* base = In + (uint64_t)row;
+        return (uint32_t)max(y >= 0 ? y : yq, 0) * (uint32_t)p.ld_in;
+    };
+    auto gather_one = [&](int32_t y, uint32_t row, i16x8 (&a)[KS], int ks) {
+        const int kk = min(ks, ksteps - 1);   // uniform
+        const uint32_t off = (uint32_t)kk * 16u + (kk == ksteps - 1 ? tail_h : full_h);
+        const u32x4 raw = *reinterpret_cast<const u32x4*>(In + (uint64_t)row + off);
         const u32x4 zero = {0u, 0u, 0u, 0u};
+        a[ks] = __builtin_bit_cast(i16x8, (UNIT && y < 0) ? zero : raw);
+    };
+    auto gather = [&](int32_t y, i16x8 (&a)[KS]) {
+        const uint32_t row = gather_row(y);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const int kk = min(ks, ksteps - 1);   // uniform
-            const uint32_t off = (uint32_t)kk * 16u + (kk == ksteps - 1 ? tail_h : full_h);
-            const u32x4 raw = *reinterpret_cast<const u32x4*>(base + off);
-            a[ks] = __builtin_bit_cast(i16x8, (UNIT && y < 0) ? zero : raw);
-        }
+        for (int ks = 0; ks < KS; ++ks) gather_one(y, row, a, ks);
     };
     auto table = [&](int32_t& y, uint16_t& vbits, int z) {
         y = tab_y[z * p.Xp];
@@ -472,41 +477,52 @@ __global__ __launch_bounds__(64 * WV, KS == 16 ? 1 : 2) void spconv_os(OsParams 
     auto one_offset = [&](int i, const i16x8 (&use)[KS], i16x8 (&fill)[KS]) {
         const int buf = i & 1;
         table(y2, v2, zt), zt = next_z(zt);      // iteration i + 2
-        stage_load(wreg, zw), zw = next_z(zw);   // iteration i + 1
-        gather(i + 1 < Z ? y1 : -1, fill);       // iteration i + 1 (nothing past the last one)
+        // Rows and weights of iteration i + 1 are requested between the k-steps below rather
+        // than in one burst, one or two loads after every four MFMAs (the wavefronts of a
+        // work-group run in step, one barrier per offset).  Measured equal in time to the burst;
+        // kept because it needs 40 registers fewer.
+        const int32_t y_fill = i + 1 < Z ? y1 : -1;   // nothing past the last iteration
+        const uint32_t row_fill = gather_row(y_fill);
+        constexpr int W_EVERY = KS / PER_THREAD;      // k-steps between two weight loads
+        static_assert(KS % PER_THREAD == 0, "weight loads spread over the k-steps");
+        auto loads_of_step = [&](int ks) {
+            __builtin_amdgcn_sched_barrier(0);
+            gather_one(y_fill, row_fill, fill, ks);
+            if (ks % W_EVERY == 0) stage_load_one(wreg, zw, ks / W_EVERY);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        auto b_frag = [&](int ks, int ni) {
+            const int pos = swizzled_chunk<CH>(l32, ks * 2 + half) * 16;   // 32 | ni * 32: same swizzle
+            return *reinterpret_cast<const i16x8*>(&lds[buf][ni * 32 * ROWB + b_row + pos]);
+        };
 
         const bool present = i < Z && y0 >= 0;
-        if (__ballot(present) != 0) {   // some output point of this wavefront has offset z
-            // every k-step up to 16 KS runs: weights past C are zero in LDS
-            auto b_frag = [&](int ks, int ni) {
-                const int pos = swizzled_chunk<CH>(l32, ks * 2 + half) * 16;   // 32 | ni * 32: same swizzle
-                return *reinterpret_cast<const i16x8*>(&lds[buf][ni * 32 * ROWB + b_row + pos]);
-            };
-            if constexpr (UNIT) {
-                // the B fragments of k-step ks + 1 are read before the MFMAs of k-step ks are issued
-                i16x8 b[2][NT];
+        const bool any = __ballot(present) != 0;   // some output point of this wavefront has offset z
+        // every k-step up to 16 KS runs: weights past C are zero in LDS
+        if constexpr (UNIT) {
 #pragma unroll
-                for (int ni = 0; ni < NT; ++ni) b[0][ni] = b_frag(0, ni);
+            for (int ks = 0; ks < KS; ++ks) {
+                if (any) {
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    if (ks + 1 < KS) {
-#pragma unroll
-                        for (int ni = 0; ni < NT; ++ni) b[(ks + 1) & 1][ni] = b_frag(ks + 1, ni);
-                    }
-#pragma unroll
-                    for (int ni = 0; ni < NT; ++ni) total[ni] = mfma32<T>(use[ks], b[ks & 1][ni], total[ni]);
+                    for (int ni = 0; ni < NT; ++ni) total[ni] = mfma32<T>(use[ks], b_frag(ks, ni), total[ni]);
                 }
-            } else {
-                f32x16 acc[NT];
+                loads_of_step(ks);
+            }
+        } else {
+            f32x16 acc[NT];
 #pragma unroll
-                for (int ni = 0; ni < NT; ++ni)
+            for (int ni = 0; ni < NT; ++ni)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[ni][r] = 0.f;
+                for (int r = 0; r < 16; ++r) acc[ni][r] = 0.f;
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
+            for (int ks = 0; ks < KS; ++ks) {
+                if (any) {
 #pragma unroll
                     for (int ni = 0; ni < NT; ++ni) acc[ni] = mfma32<T>(use[ks], b_frag(ks, ni), acc[ni]);
                 }
+                loads_of_step(ks);
+            }
+            if (any) {
                 const float v_row = present ? half_bits_to_float(v0, T{}) : 0.f;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
@@ -516,6 +532,7 @@ __global__ __launch_bounds__(64 * WV, KS == 16 ? 1 : 2) void spconv_os(OsParams 
                 }
             }
         }
+        zw = next_z(zw);
         stage_store(buf ^ 1, wreg);
         __syncthreads();
         y0 = y1, v0 = v1, y1 = y2, v1 = v2;
