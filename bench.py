@@ -379,7 +379,7 @@ def main():
     torch.cuda.empty_cache()
     if not args.no_extra:
         others = {}
-        for name in ("cfg5", "cfg4", "cfg2", "cfg1"):
+        for name in ("cfg3_f16", "cfg5", "cfg4", "cfg2", "cfg1"):
             if name == args.workload:
                 continue
             r, keep = run_workload(torch, I, name, args.steps, args.warmup)

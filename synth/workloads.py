@@ -237,11 +237,12 @@ def make_config(name: str, seed: int = 0, shuffle: bool = True) -> dict:
         nnz = int(round(0.10 * M * K))
         row, col, val = random_coo(M, K, nnz, seed, "f16", 0.02, shuffle)
         cfg = dict(kind="group", M=M, K=K, N=N, a_dtype="f16", b_dtype="f16", c_dtype="f16")
-    elif name == "cfg3":  # graph aggregation shape: 2^20 rows, Zipf(1.2) degrees, mean 16, N=128
+    elif name in ("cfg3", "cfg3_f16"):  # graph aggregation shape: 2^20 rows, Zipf(1.2) degrees, mean 16, N=128
         M = K = 1 << 20
         N = 128
-        row, col, val = zipf_rows_coo(M, K, 1.2, 16.0, seed, "f32", "inv_deg", None, shuffle)
-        cfg = dict(kind="group", M=M, K=K, N=N, a_dtype="f32", b_dtype="f32", c_dtype="f32")
+        dt = "f32" if name == "cfg3" else "f16"    # the paper reports this experiment in both precisions
+        row, col, val = zipf_rows_coo(M, K, 1.2, 16.0, seed, dt, "inv_deg", None, shuffle)
+        cfg = dict(kind="group", M=M, K=K, N=N, a_dtype=dt, b_dtype=dt, c_dtype=dt)
     elif name == "cfg4":  # 8192^2 bf16, 32x32 blocks, 10% of blocks, N=512
         M = K = 8192
         N = 512

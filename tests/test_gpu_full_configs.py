@@ -16,10 +16,10 @@ from helpers import assert_spmm_close, to_f32
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 
-EXPECTED_G = {"cfg1": 2, "cfg2": 16, "cfg3": 4, "cfg4": 4, "cfg5": 4}
+EXPECTED_G = {"cfg1": 2, "cfg2": 16, "cfg3": 4, "cfg3_f16": 4, "cfg4": 4, "cfg5": 4}
 
 
-@pytest.mark.parametrize("name", synth.CONFIG_NAMES)
+@pytest.mark.parametrize("name", synth.CONFIG_NAMES + ("cfg3_f16",))   # + the fp16 twin of cfg3
 def test_full_config(name):
     import paper_2510_17505_amd as I
     t0 = time.time()
