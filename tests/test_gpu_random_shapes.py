@@ -77,3 +77,52 @@ def test_random_blockgroupcoo_problem(seed):
     absprod = oracle.spmm_blockgroupcoo(M, K, N, bM, bK, AM, AK, np.abs(av), np.abs(B))
     C = I.insum_spmm_blockgroupcoo(A, values_to_torch(B, dtype))
     assert_spmm_close(C.float().cpu().numpy(), C64, absprod, RTOL[dtype], f"seed {seed}")
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_sparse_convolution_problem(seed):
+    """Random maps (repeated triples, repeated (x, z) pairs with different y, empty offsets,
+    sparse and dense occupancy, all three schedules), channel counts on and off the matrix-core
+    conditions, unit and general values, fresh and accumulated output."""
+    import paper_2510_17505_amd as I
+    from gpu_util import bits, storage_to_torch, torch_to_storage
+    rng = np.random.default_rng(3000 + seed)
+    X = int(rng.integers(1, 700))
+    Y = int(rng.integers(1, 700))
+    Z = int(rng.choice([1, 2, 3, 8, 27, 27, 40, 125]))
+    C = int(rng.choice([8, 16, 24, 32, 40, 64, 72, 128, 136, 256, 12, 20, 264]))
+    M = int(rng.choice([1, 8, 31, 32, 64, 65, 96, 128, 130, 200, 256]))
+    dtype = ["f16", "bf16", "f32"][seed % 3] if seed % 5 else "f16"
+    g = int(rng.choice([0, 1, 2, 3, 8, 16, 32, 33, 64, 256]))
+    density = float(rng.choice([0.0005, 0.01, 0.05, 0.3, 0.8]))
+    nnz = int(density * X * Z) + int(rng.integers(0, 3))
+    unit = bool(seed % 2)
+    print(f"[random spconv] seed={seed} X={X} Y={Y} Z={Z} C={C} M={M} g={g} {dtype} nnz={nnz} unit={unit}",
+          flush=True)
+    mx = rng.integers(0, X, nnz).astype(np.int32)
+    my = rng.integers(0, Y, nnz).astype(np.int32)
+    mz = rng.integers(0, Z, nnz).astype(np.int32)
+    mv = np.ones(nnz, np.float32) if unit else synth.round_to_dtype(rng.standard_normal(nnz), dtype)
+    st = synth.storage_array(mv, dtype)
+    want = oracle.map_to_groupcoo(X, Y, Z, mx, my, mz, st, g or None)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+    Map = I.insum_map_to_groupcoo(X, Y, Z, dev(mx), dev(my), dev(mz), storage_to_torch(st, dtype), g)
+    gg, MZ, MX, MY, MV = want
+    assert Map.g == gg and Map.G == MZ.shape[0]
+    assert np.array_equal(Map.MAPZ.cpu().numpy(), MZ) and np.array_equal(Map.MAPX.cpu().numpy(), MX)
+    assert np.array_equal(Map.MAPY.cpu().numpy(), MY)
+    assert np.array_equal(bits(torch_to_storage(Map.MAPV)), bits(MV))
+    In = synth.round_to_dtype(rng.standard_normal((Y, C)), dtype)
+    W = synth.round_to_dtype(rng.standard_normal((Z, C, M)), dtype)
+    mv32 = to_f32(MV, dtype)
+    O0 = rng.standard_normal((X, M)).astype(np.float32) if seed % 3 == 0 else None
+    O64 = oracle.spconv_groupcoo(X, C, M, MZ, MX, MY, mv32, In, W, Out_init=O0)
+    absprod = oracle.spconv_groupcoo(X, C, M, MZ, MX, MY, np.abs(mv32), np.abs(In), np.abs(W),
+                                     Out_init=None if O0 is None else np.abs(O0))
+    if O0 is None:
+        Out = I.insum_spconv_groupcoo(Map, values_to_torch(In, dtype), values_to_torch(W, dtype))
+    else:
+        Out = torch.from_numpy(O0.copy()).cuda()
+        I.insum_spconv_groupcoo(Map, values_to_torch(In, dtype), values_to_torch(W, dtype), Out=Out,
+                                accumulate=True)
+    assert_spmm_close(Out.cpu().numpy(), O64, absprod, 1e-5, f"seed {seed}")
