@@ -247,10 +247,12 @@ size_t insum_spconv_groupcoo_workspace_bytes(int64_t X, int64_t Z, int64_t C, in
  *   workspace   device scratch, at least insum_spconv_groupcoo_workspace_bytes(...) bytes
  *               (INSUM_ERR_CAPACITY otherwise); may be NULL when that is 0
  *   reuse_map_tables  0: the call derives its tables from the map.  Nonzero: the caller
- *               guarantees that `workspace` still holds what an earlier call with the same
- *               X, Z, C, M, G, g, dt and the same MAPZ/MAPX/MAPY/MAPV contents left there (the
- *               layers of a network that share one kernel map), so that step is skipped.
- *               In, W, Out and accumulate may differ between such calls.
+ *               guarantees that `workspace` (same address) still holds what an earlier call
+ *               with the same X, Z, G, g, dt and the same MAPZ/MAPX/MAPY/MAPV contents left
+ *               there (the layers of a network that share one kernel map), so that step is
+ *               skipped.  In, W, Out, C, M and accumulate may differ between such calls; the
+ *               workspace must be large enough for each of them, and every one of them must
+ *               be a shape with a nonzero insum_spconv_groupcoo_workspace_bytes.
  *
  * Products are exact and sums are formed in fp32.  16-bit types with C a multiple of 8, at
  * most 256, ld_in a multiple of 8 and In 16-byte aligned run on the matrix cores, in one of

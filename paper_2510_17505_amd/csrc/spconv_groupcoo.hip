@@ -595,11 +595,13 @@ OsLayout os_layout(int64_t X, int64_t Z, int64_t C, int64_t M, int64_t slots) {
     L.Mp = ceil_div(M, 128) * 128;
     L.Cp = 16 * ks_for(C);
     size_t b = 256;   // slack for aligning the caller's pointer
+    // what depends on the map only comes first, so that calls with other channel counts find it
+    // at the same place (reuse_map_tables)
     L.off_tabY = b, b += align_up((size_t)(Z * L.Xp) * 4, 256);
     L.off_tabV = b, b += align_up((size_t)(Z * L.Xp) * 2, 256);
-    L.off_wt = b, b += align_up((size_t)(Z * L.Mp * L.Cp) * 2, 256);
     L.off_count = b, b += 256;   // overflow counter, non-unit flag
     L.off_ovf = b, b += align_up((size_t)std::max<int64_t>(slots, 1) * 4, 256);
+    L.off_wt = b, b += align_up((size_t)(Z * L.Mp * L.Cp) * 2, 256);
     L.bytes = b;
     return L;
 }

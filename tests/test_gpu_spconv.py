@@ -268,16 +268,17 @@ def test_spconv_full_size_properties_and_samples():
 
 @pytest.mark.parametrize("values", ["ones", "normal"])
 def test_spconv_reuses_the_map_tables_across_layers(values):
-    """Two layers over one kernel map: the second call skips the table build and must still
-    match the oracle, with other features, weights and widths of the same tile class."""
+    """Three layers over one kernel map: the later calls skip the table build and must still
+    match the oracle, with other features, weights and channel counts."""
     P, mx, my, mz, mv = synth.voxel_kernel_map(13, 0.3, seed=11, dtype="f16", values=values)
     st = synth.storage_array(mv, "f16")
     _, MZ, MX, MY, MV = oracle.map_to_groupcoo(P, P, 27, mx, my, mz, st, None)
     Map = I.insum_map_to_groupcoo(P, P, 27, _i32(mx), _i32(my), _i32(mz), storage_to_torch(st, "f16"))
-    C, M = 64, 96
-    ws = torch.empty(I.insum_spconv_groupcoo_workspace_bytes(Map, C, M, torch.float16), dtype=torch.uint8,
-                     device="cuda")
-    for layer, reuse in ((0, False), (1, True), (2, True)):
+    shapes = ((64, 96), (64, 96), (128, 32), (32, 256))
+    ws = torch.empty(max(I.insum_spconv_groupcoo_workspace_bytes(Map, C, M, torch.float16) for C, M in shapes),
+                     dtype=torch.uint8, device="cuda")
+    for layer, (C, M) in enumerate(shapes):
+        reuse = layer > 0
         In = _features(P, C, 20 + layer, "f16")
         W = _features(C, M, 30 + layer, "f16", lead=27)
         got = I.insum_spconv_groupcoo(Map, values_to_torch(In, "f16"), values_to_torch(W, "f16"),
