@@ -56,6 +56,39 @@ def _time_launches(torch, fn, steps, warmup):
     return start.elapsed_time(stop) / steps      # ms per step
 
 
+def _per_launch_times(torch, fn, launches, flush=None):
+    """Each launch timed on its own (HIP events around it); `flush`, when given, runs before
+    every launch outside its timed window.  Returns (median, min) in ms."""
+    times = []
+    for _ in range(launches):
+        if flush is not None:
+            flush()
+        start = torch.cuda.Event(enable_timing=True)
+        stop = torch.cuda.Event(enable_timing=True)
+        start.record()
+        fn()
+        stop.record()
+        torch.cuda.synchronize()
+        times.append(start.elapsed_time(stop))
+    times.sort()
+    return times[len(times) // 2], times[0]
+
+
+def launch_statistics(torch, fn, launches=50):
+    """Warm (back to back) and cold (a 1 GiB buffer is rewritten before every launch, which
+    evicts the 8 x 4 MiB L2 and the 256 MB Infinity Cache) per-launch times of the headline."""
+    for _ in range(5):
+        fn()
+    warm = _per_launch_times(torch, fn, launches)
+    junk = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    cold = _per_launch_times(torch, fn, launches, flush=lambda: junk.add_(1.0))
+    del junk
+    return {"launches": launches, "warm_median_ms": warm[0], "warm_min_ms": warm[1],
+            "cold_median_ms": cold[0], "cold_min_ms": cold[1],
+            "note": "single launches between their own events (includes ~launch latency); ms_per_step is the "
+                    "mean over back-to-back launches"}
+
+
 def prepare(torch, I, name):
     """Generate a workload, move it to the device and convert it with the library."""
     import synth
@@ -373,6 +406,14 @@ def main():
         "model_bytes_per_launch": res["model_bytes"],
         "conversion_ms": res["conversion_ms"],
     }
+    if cfg["kind"] == "group":
+        ws = torch.empty(I.insum_spmm_groupcoo_workspace_bytes(cfg["M"], cfg["N"], A.G, A.g), dtype=torch.uint8,
+                         device="cuda")
+        line["launch_statistics"] = launch_statistics(
+            torch, lambda: I.insum_spmm_groupcoo(A, B, C_out=C, workspace=ws))
+        del ws
+    else:
+        line["launch_statistics"] = launch_statistics(torch, lambda: I.insum_spmm_blockgroupcoo(A, B, C_out=C))
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(cfg, A, res["nnz"])
     del A, B, C, cfg
