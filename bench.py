@@ -303,6 +303,18 @@ def vendor_context(torch, I, steps, warmup):
     ms = _time_launches(torch, lambda: torch.matmul(a, b), steps, warmup)
     out["dense_4096_f16"] = {"library": "torch.matmul (hipBLASLt)", "ms": ms,
                              "tflops": 2.0 * 4096 ** 3 / ms / 1e9}
+    # Section 6.2 asks at which sparsity the block-sparse product beats the dense one: the same
+    # 4096^2 fp16 matrix in 32x32 blocks at several block densities, N = 4096.
+    sweep = []
+    for density in (0.05, 0.1, 0.2, 0.3, 0.4, 0.5, 0.75, 1.0):
+        row, col, val = synth.random_block_coo(4096, 4096, 32, 32, seed=0, dtype="f16", block_density=density)
+        A = I.insum_coo_to_blockgroupcoo(4096, 4096, torch.from_numpy(row).cuda(), torch.from_numpy(col).cuda(),
+                                         _to_device(torch, val, "f16"), 32, 32, g=0)
+        C = torch.empty((4096, 4096), dtype=torch.float16, device="cuda")
+        t = _time_launches(torch, lambda: I.insum_spmm_blockgroupcoo(A, b, C_out=C), steps, warmup)
+        sweep.append({"block_density": density, "g": A.g, "ms": t, "dense_ms_over_ms": ms / t})
+        del A, C
+    out["block_density_sweep_4096_f16"] = sweep
     return out
 
 
