@@ -294,7 +294,7 @@ __global__ void fill_zero_rows(float* out, int64_t rows, int64_t cols, int64_t l
 // ---------------------------------------------------------------------------------------------
 struct OsParams {
     int64_t X, Z, C, M;
-    int64_t Xp;           // X rounded up to a multiple of 256 (table row length)
+    int64_t Xp;           // X rounded up to a multiple of 512 (table row length)
     int32_t* tabY;        // [Z][Xp]
     uint16_t* tabV;       // [Z][Xp]
     uint16_t* Wt;         // [Z][Mp][Cp]
@@ -353,10 +353,11 @@ __device__ inline int swizzled_chunk(int n, int ch) {
 //          the rows of an offset are gathered once for 128 output channels.  The fragments of
 //          absent input points are replaced by zeros before they are used.
 //   !UNIT  general values: NT = 2 and a separate accumulator per offset, scaled by the values.
-// (KS = 16 is built for one wavefront per SIMD: its A fragment sets alone take 128 registers)
-template <typename T, int KS, int NT, bool UNIT, int WV>
+// (the general variant with KS = 16 is built for one wavefront per SIMD: it needs all 256 registers)
+template <typename T, int KS, int NT, bool UNIT, int WV, int RT>
 __global__ __launch_bounds__(64 * WV, KS == 16 ? 1 : 2) void spconv_os(OsParams p) {
-    constexpr int THREADS = 64 * WV, ROWS = 32 * WV;   // WV wavefronts, 32 output points each
+    // WV wavefronts, each with RT row tiles of 32 output points
+    constexpr int THREADS = 64 * WV, ROWS = 32 * WV * RT;
     if ((*p.nonunit != 0) == UNIT) return;   // the other variant runs
     constexpr int CH = 2 * KS;             // 16-byte chunks per weight row
     constexpr int ROWB = CH * 16;          // bytes per weight row in LDS
@@ -379,16 +380,15 @@ __global__ __launch_bounds__(64 * WV, KS == 16 ? 1 : 2) void spconv_os(OsParams 
     const bool odd = p.C % 16 == 8;   // the last k-step holds 8 channels only
     const uint16_t* const In = static_cast<const uint16_t*>(p.In);
 
-    // Offsets are visited cyclically from a start that differs between work-groups.  All
-    // work-groups march through the offsets at about the same pace; started together they would
-    // all stage the same 16 KB of weights at the same time, from the few L2 channels that hold it.
+    // Offsets are visited cyclically from a start that differs between work-groups.
     const int Z = (int)p.Z;
     const int z_start = (int)((xblk * 7 + mt * 3) % Z);
     auto next_z = [&](int z) { return z + 1 == Z ? 0 : z + 1; };
 
-    // Table cells of this lane's output point.
-    const int32_t* const tab_y = p.tabY + (xblk * ROWS + wv * 32 + l32);
-    const uint16_t* const tab_v = p.tabV + (xblk * ROWS + wv * 32 + l32);
+    // Table cells of this lane's output points: row tile rt is 32 cells further on.
+    const int64_t x_first = xblk * ROWS + wv * (32 * RT);
+    const int32_t* const tab_y = p.tabY + (x_first + l32);
+    const uint16_t* const tab_v = p.tabV + (x_first + l32);
 
     // Weight staging: thread owns chunk tid % CH of rows tid / CH + ROWS_PER_ROUND j.
     const int st_n = tid / CH, st_ch = tid % CH;
@@ -400,10 +400,6 @@ __global__ __launch_bounds__(64 * WV, KS == 16 ? 1 : 2) void spconv_os(OsParams 
     // loads be consumed while newer ones are in flight)
     auto stage_load_one = [&](u32x4 (&reg)[PER_THREAD], int z, int j) {
         reg[j] = *reinterpret_cast<const u32x4*>(w_src + z * w_next + j * w_round);
-    };
-    auto stage_load = [&](u32x4 (&reg)[PER_THREAD], int z) {
-#pragma unroll
-        for (int j = 0; j < PER_THREAD; ++j) stage_load_one(reg, z, j);
     };
     auto stage_store = [&](int buf, const u32x4 (&reg)[PER_THREAD]) {
 #pragma unroll
@@ -427,88 +423,103 @@ __global__ __launch_bounds__(64 * WV, KS == 16 ? 1 : 2) void spconv_os(OsParams 
         yq = max(yq, __builtin_amdgcn_update_dpp(yq, yq, 0x4E, 0xF, 0xF, false));
         return (uint32_t)max(y >= 0 ? y : yq, 0) * (uint32_t)p.ld_in;
     };
-    auto gather_one = [&](int32_t y, uint32_t row, i16x8 (&a)[KS], int ks) {
+    auto gather_one = [&](int32_t y, uint32_t row, int ks) {
         const int kk = min(ks, ksteps - 1);   // uniform
         const uint32_t off = (uint32_t)kk * 16u + (kk == ksteps - 1 ? tail_h : full_h);
         const u32x4 raw = *reinterpret_cast<const u32x4*>(In + (uint64_t)row + off);
         const u32x4 zero = {0u, 0u, 0u, 0u};
-        a[ks] = __builtin_bit_cast(i16x8, (UNIT && y < 0) ? zero : raw);
+        return __builtin_bit_cast(i16x8, (UNIT && y < 0) ? zero : raw);
     };
-    auto gather = [&](int32_t y, i16x8 (&a)[KS]) {
-        const uint32_t row = gather_row(y);
+    auto table = [&](int32_t (&y)[RT], uint16_t (&vbits)[RT], int z) {
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) gather_one(y, row, a, ks);
-    };
-    auto table = [&](int32_t& y, uint16_t& vbits, int z) {
-        y = tab_y[z * p.Xp];
-        vbits = tab_v[z * p.Xp];   // unspecified where y < 0
+        for (int rt = 0; rt < RT; ++rt) {
+            y[rt] = tab_y[z * p.Xp + rt * 32];
+            vbits[rt] = tab_v[z * p.Xp + rt * 32];   // unspecified where y < 0
+        }
     };
 
-    f32x16 total[NT];
+    f32x16 total[RT][NT];
 #pragma unroll
-    for (int ni = 0; ni < NT; ++ni)
+    for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) total[ni][r] = 0.f;
+        for (int ni = 0; ni < NT; ++ni)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) total[rt][ni][r] = 0.f;
 
     u32x4 wreg[PER_THREAD];
-    // Software pipeline: rows and weights are requested one offset ahead (two sets of A
-    // fragments), table cells two offsets ahead.  Within an iteration the table load is issued
-    // first: the next iteration needs it first, and the load counter is in order.  (Loads here
-    // mostly hit the L2, about 150 clocks away; an iteration lasts several thousand.)
-    i16x8 a[KS], a1[KS];
-    int32_t y0, y1, y2 = -1;
-    uint16_t v0, v1, v2 = 0;   // value bits; converted where they are used
+    // Software pipeline.  One set of A fragments: the fragment of k-step ks is requested for the
+    // next offset right after the MFMAs that read it for this one, so rows and weights run one
+    // offset ahead and table cells two.  (Loads here mostly hit the L2, a few hundred clocks
+    // away; an iteration lasts several thousand.)  The table load is issued first in an
+    // iteration: the next iteration needs it first, and the load counter is in order.
+    i16x8 a[RT][KS];
+    int32_t y0[RT], y1[RT], y2[RT];
+    uint16_t v0[RT], v1[RT], v2[RT];   // value bits; converted where they are used
     // Z >= 1 here.  zw / zt: the offsets whose weights and table cells are requested next.
     int zw = z_start, zt = z_start;
-    stage_load(wreg, zw), zw = next_z(zw);
+#pragma unroll
+    for (int j = 0; j < PER_THREAD; ++j) stage_load_one(wreg, zw, j);
+    zw = next_z(zw);
     table(y0, v0, zt), zt = next_z(zt);
     table(y1, v1, zt), zt = next_z(zt);
-    gather(y0, a);
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        const uint32_t row = gather_row(y0[rt]);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) a[rt][ks] = gather_one(y0[rt], row, ks);
+    }
     stage_store(0, wreg);
     __syncthreads();
 
     // byte offset of this lane's B fragment for k-step 0, column block 0, inside a buffer
     const int b_row = l32 * ROWB;
+    constexpr int W_EVERY = KS / PER_THREAD;   // k-steps between two weight loads
+    static_assert(KS % PER_THREAD == 0, "weight loads spread over the k-steps");
 
-    // One offset (iteration i): `use` holds its rows, `fill` receives those of iteration i + 1.  The
-    // loop below is unrolled twice so that the two fragment sets alternate by name; a register-to-
-    // register rotation would have to wait for the loads it moves.  An iteration at or past Z (one,
-    // when Z is odd) runs with every point absent.
-    auto one_offset = [&](int i, const i16x8 (&use)[KS], i16x8 (&fill)[KS]) {
+    const int iterations = Z;
+    for (int i = 0; i < iterations; ++i) {
         const int buf = i & 1;
         table(y2, v2, zt), zt = next_z(zt);      // iteration i + 2
-        // Rows and weights of iteration i + 1 are requested between the k-steps below rather
-        // than in one burst, one or two loads after every four MFMAs (the wavefronts of a
-        // work-group run in step, one barrier per offset).  Measured equal in time to the burst;
-        // kept because it needs 40 registers fewer.
-        const int32_t y_fill = i + 1 < Z ? y1 : -1;   // nothing past the last iteration
-        const uint32_t row_fill = gather_row(y_fill);
-        constexpr int W_EVERY = KS / PER_THREAD;      // k-steps between two weight loads
-        static_assert(KS % PER_THREAD == 0, "weight loads spread over the k-steps");
-        auto loads_of_step = [&](int ks) {
-            __builtin_amdgcn_sched_barrier(0);
-            gather_one(y_fill, row_fill, fill, ks);
-            if (ks % W_EVERY == 0) stage_load_one(wreg, zw, ks / W_EVERY);
-            __builtin_amdgcn_sched_barrier(0);
-        };
+        int32_t y_fill[RT];
+        uint32_t row_fill[RT];
+        bool present[RT];
+        bool any = false;
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            y_fill[rt] = i + 1 < Z ? y1[rt] : -1;   // nothing past the last iteration
+            row_fill[rt] = gather_row(y_fill[rt]);
+            present[rt] = y0[rt] >= 0;
+            any |= __ballot(present[rt]) != 0;      // some output point of this wavefront has offset z
+        }
         auto b_frag = [&](int ks, int ni) {
             const int pos = swizzled_chunk<CH>(l32, ks * 2 + half) * 16;   // 32 | ni * 32: same swizzle
             return *reinterpret_cast<const i16x8*>(&lds[buf][ni * 32 * ROWB + b_row + pos]);
         };
-
-        const bool present = i < Z && y0 >= 0;
-        const bool any = __ballot(present) != 0;   // some output point of this wavefront has offset z
+        // Rows and weights of iteration i + 1 are requested between the k-steps, one or two
+        // loads after every group of MFMAs.
+        auto loads_of_step = [&](int ks) {
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) a[rt][ks] = gather_one(y_fill[rt], row_fill[rt], ks);
+            if (ks % W_EVERY == 0) stage_load_one(wreg, zw, ks / W_EVERY);
+            __builtin_amdgcn_sched_barrier(0);
+        };
         // every k-step up to 16 KS runs: weights past C are zero in LDS
         if constexpr (UNIT) {
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 if (any) {
 #pragma unroll
-                    for (int ni = 0; ni < NT; ++ni) total[ni] = mfma32<T>(use[ks], b_frag(ks, ni), total[ni]);
+                    for (int ni = 0; ni < NT; ++ni) {
+                        const i16x8 b = b_frag(ks, ni);
+#pragma unroll
+                        for (int rt = 0; rt < RT; ++rt) total[rt][ni] = mfma32<T>(a[rt][ks], b, total[rt][ni]);
+                    }
                 }
                 loads_of_step(ks);
             }
         } else {
+            static_assert(UNIT || RT == 1, "general values: one row tile per wavefront");
             f32x16 acc[NT];
 #pragma unroll
             for (int ni = 0; ni < NT; ++ni)
@@ -518,42 +529,43 @@ __global__ __launch_bounds__(64 * WV, KS == 16 ? 1 : 2) void spconv_os(OsParams 
             for (int ks = 0; ks < KS; ++ks) {
                 if (any) {
 #pragma unroll
-                    for (int ni = 0; ni < NT; ++ni) acc[ni] = mfma32<T>(use[ks], b_frag(ks, ni), acc[ni]);
+                    for (int ni = 0; ni < NT; ++ni) acc[ni] = mfma32<T>(a[0][ks], b_frag(ks, ni), acc[ni]);
                 }
                 loads_of_step(ks);
             }
             if (any) {
-                const float v_row = present ? half_bits_to_float(v0, T{}) : 0.f;
+                const float v_row = present[0] ? half_bits_to_float(v0[0], T{}) : 0.f;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const float vr = __shfl(v_row, 8 * (r / 4) + 4 * half + (r % 4));
 #pragma unroll
-                    for (int ni = 0; ni < NT; ++ni) total[ni][r] = fmaf(vr, acc[ni][r], total[ni][r]);
+                    for (int ni = 0; ni < NT; ++ni) total[0][ni][r] = fmaf(vr, acc[ni][r], total[0][ni][r]);
                 }
             }
         }
         zw = next_z(zw);
         stage_store(buf ^ 1, wreg);
         __syncthreads();
-        y0 = y1, v0 = v1, y1 = y2, v1 = v2;
-    };
-    for (int i = 0; i < Z; i += 2) {
-        one_offset(i, a, a1);
-        one_offset(i + 1, a1, a);
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+            y0[rt] = y1[rt], v0[rt] = v1[rt], y1[rt] = y2[rt], v1[rt] = v2[rt];
     }
 
-    // accumulator register r: output point 8 (r / 4) + 4 (lane / 32) + r % 4 of the wavefront's
-    // 32, output channel m0 + 32 ni + lane % 32
+    // accumulator register r: output point 8 (r / 4) + 4 (lane / 32) + r % 4 of the row tile,
+    // output channel m0 + 32 ni + lane % 32
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int64_t x = xblk * ROWS + wv * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-        if (x < p.X) {
+    for (int rt = 0; rt < RT; ++rt) {
 #pragma unroll
-            for (int ni = 0; ni < NT; ++ni) {
-                const int64_t m = m0 + ni * 32 + l32;
-                if (m < p.M) {
-                    float* out = p.Out + x * p.ld_out + m;
-                    *out = p.accumulate ? *out + total[ni][r] : total[ni][r];
+        for (int r = 0; r < 16; ++r) {
+            const int64_t x = x_first + rt * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+            if (x < p.X) {
+#pragma unroll
+                for (int ni = 0; ni < NT; ++ni) {
+                    const int64_t m = m0 + ni * 32 + l32;
+                    if (m < p.M) {
+                        float* out = p.Out + x * p.ld_out + m;
+                        *out = p.accumulate ? *out + total[rt][ni][r] : total[rt][ni][r];
+                    }
                 }
             }
         }
@@ -591,7 +603,7 @@ inline int ks_for(int64_t C) { return C <= 32 ? 2 : C <= 64 ? 4 : C <= 128 ? 8 :
 
 OsLayout os_layout(int64_t X, int64_t Z, int64_t C, int64_t M, int64_t slots) {
     OsLayout L;
-    L.Xp = ceil_div(X, 256) * 256;
+    L.Xp = ceil_div(X, 512) * 512;
     L.Mp = ceil_div(M, 128) * 128;
     L.Cp = 16 * ks_for(C);
     size_t b = 256;   // slack for aligning the caller's pointer
@@ -611,25 +623,27 @@ OsLayout os_layout(int64_t X, int64_t Z, int64_t C, int64_t M, int64_t slots) {
 bool os_shape_ok(int64_t X, int64_t Z, int64_t C, int64_t M, int64_t slots, insum_dtype dt) {
     // (row offsets into In are 32-bit element counts: checked by the caller, which knows Y and ld_in)
     return dt != INSUM_F32 && C % 8 == 0 && C >= 8 && C <= 256 && X > 0 && Z > 0 && M > 0 &&
-           slots * 16 >= X * Z && slots < (1LL << 31) && Z * (ceil_div(X, 256) * 256) < (1LL << 38) &&
+           slots * 16 >= X * Z && slots < (1LL << 31) && Z * (ceil_div(X, 512) * 512) < (1LL << 38) &&
            Z * (ceil_div(M, 128) * 128) * 256 < (1LL << 38) &&
            ceil_div(X, 128) * ceil_div(M, 64) + 8 * ceil_div(M, 64) < (1LL << 31);
 }
 
-template <typename T, int KS, int NT, bool UNIT, int WV>
+template <typename T, int KS, int NT, bool UNIT, int WV, int RT>
 void launch_os_variant(OsParams o, hipStream_t s) {
     o.m_tiles = (int32_t)ceil_div(o.M, 32 * NT);
-    o.x_blocks = (int32_t)ceil_div(o.X, 32 * WV);
+    o.x_blocks = (int32_t)ceil_div(o.X, 32 * WV * RT);
     const unsigned grid = (unsigned)(ceil_div(o.x_blocks, 8) * 8 * o.m_tiles);
-    hipLaunchKernelGGL((spconv_os<T, KS, NT, UNIT, WV>), dim3(grid), dim3(64 * WV), 0, s, o);
+    hipLaunchKernelGGL((spconv_os<T, KS, NT, UNIT, WV, RT>), dim3(grid), dim3(64 * WV), 0, s, o);
 }
 
 template <typename T, int KS>
 void launch_os_both(const OsParams& o, hipStream_t s) {
     // UNIT with KS <= 8 fits two wavefronts per SIMD: eight wavefronts (256 output points) share
     // one staged weight tile, which halves the weight traffic per MFMA (5 % faster than four).
-    launch_os_variant<T, KS, (KS == 16 ? 2 : 4), true, (KS == 16 ? 4 : 8)>(o, s);
-    launch_os_variant<T, KS, 2, false, 4>(o, s);
+    // RT = 2 (two row tiles per wavefront share every B fragment: half the LDS reads) was measured
+    // too: 4 % slower at 256 registers, so one row tile it is.
+    launch_os_variant<T, KS, (KS == 16 ? 2 : 4), true, (KS == 16 ? 4 : 8), 1>(o, s);
+    launch_os_variant<T, KS, 2, false, 4, 1>(o, s);
 }
 
 template <typename T>
