@@ -274,6 +274,31 @@ def group_size_sweep(torch, I, steps, warmup):
     return out
 
 
+def width_sweep(torch, I, steps, warmup):
+    """GroupCOO SpMM on the cfg3 matrix for dense widths N = 8 ... 256 in fp32 and fp16: how the
+    gather-bound kernel behaves from 16-byte to 1 KiB rows of B."""
+    import synth
+    cfg = synth.make_config("cfg3")
+    M, K = cfg["M"], cfg["K"]
+    A32 = I.insum_coo_to_groupcoo(M, K, torch.from_numpy(cfg["row"]).cuda(), torch.from_numpy(cfg["col"]).cuda(),
+                                  torch.from_numpy(cfg["val"]).cuda(), g=0)
+    nnz = int(cfg["row"].size)
+    out = []
+    for name, dt, es in (("f32", torch.float32, 4), ("f16", torch.float16, 2)):
+        A = A32 if es == 4 else I.GroupCOO(A32.M, A32.K, A32.g, A32.AM, A32.AK, A32.AV.half())
+        for N in (8, 16, 32, 64, 128, 256):
+            B = torch.randn((K, N), device="cuda").to(dt)
+            C = torch.empty((M, N), dtype=dt, device="cuda")
+            ws = torch.empty(I.insum_spmm_groupcoo_workspace_bytes(M, N, A.G, A.g), dtype=torch.uint8,
+                             device="cuda")
+            ms = _time_launches(torch, lambda: I.insum_spmm_groupcoo(A, B, C_out=C, workspace=ws), steps, warmup)
+            model = A.G * A.g * (N * es + 4 + es) + 4 * A.G + M * N * es
+            out.append({"dtype": name, "N": N, "row_bytes": N * es, "ms": ms, "gflops": 2.0 * nnz * N / ms / 1e6,
+                        "model_gbs": model / ms / 1e6, "gathers_per_s": A.G * A.g / ms * 1e3})
+            del B, C, ws
+    return out
+
+
 def vendor_context(torch, I, steps, warmup):
     """Context only (not part of the library): the vendor SpMM that PyTorch dispatches to
     (rocSPARSE CSR) on cfg3 and cfg2, and the dense GEMM (hipBLASLt) on the sweep shape - the
@@ -367,6 +392,8 @@ def main():
                     help="only run the group-size sweep on the paper's ablation shape")
     ap.add_argument("--context", action="store_true",
                     help="only time the vendor libraries PyTorch dispatches to (context, not product)")
+    ap.add_argument("--width-sweep", action="store_true",
+                    help="only run the GroupCOO SpMM of cfg3 for N = 8 ... 256 in fp32 and fp16")
     ap.add_argument("--spconv", action="store_true",
                     help="only time the sparse-convolution workload (Section 6.4)")
     ap.add_argument("--peaks", action="store_true", help="only run the achievable-peak microbenchmarks")
@@ -398,6 +425,9 @@ def main():
         return
     if args.context:
         print(json.dumps({"vendor_context": vendor_context(torch, I, args.steps, args.warmup)}))
+        return
+    if args.width_sweep:
+        print(json.dumps({"width_sweep": width_sweep(torch, I, args.steps, args.warmup)}))
         return
     if args.spconv:
         print(json.dumps({"spconv": run_spconv(torch, I, args.steps, args.warmup)}))
