@@ -164,6 +164,26 @@ insum_status insum_spmm_groupcoo(int64_t M, int64_t K, int64_t N, int64_t G, int
                                  void* C, int64_t ldc, insum_dtype c_dt, int accumulate,
                                  void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * insum_spmm_groupcoo for callers that cannot allocate device memory or pass a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments (without the workspace), same kernels and same results up to fp32 summation
+ * order.  The partial sums of rows shared between work ranges live in a device array of
+ * 32 MiB that is part of the library image (every GPU the library runs on holds its copy
+ * until the process ends); the call performs no allocation and no free, and does not
+ * synchronise.  The work is cut into fewer ranges when the usual number of them would not
+ * fit the array; INSUM_ERR_CAPACITY when even one range does not fit (N above 4 194 304).
+ * The device that owns `stream` must be the current device.  All calls on one GPU share the
+ * array: calls that may overlap on one GPU (different streams, several host threads) race
+ * and must be serialised by the caller.
+ */
+insum_status insum_spmm_groupcoo_noalloc(int64_t M, int64_t K, int64_t N, int64_t G, int32_t g,
+                                         const int32_t* AM, const int32_t* AK, const void* AV,
+                                         insum_dtype a_dt,
+                                         const void* B, int64_t ldb, insum_dtype b_dt,
+                                         void* C, int64_t ldc, insum_dtype c_dt, int accumulate,
+                                         void* stream);
+
 /* ---------------------------------------------------------------------------------- */
 /* SpMM over BlockGroupCOO (Section 4.1, BlockGroupCOO Einsum)                         */
 /* ---------------------------------------------------------------------------------- */

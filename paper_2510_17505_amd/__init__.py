@@ -23,6 +23,7 @@ from .api import (  # noqa: F401
     insum_spmm_blockgroupcoo,
     insum_spmm_blockgroupcoo_workspace_bytes,
     insum_spmm_groupcoo,
+    insum_spmm_groupcoo_noalloc,
     insum_spmm_groupcoo_workspace_bytes,
     insum_status_string,
     insum_version,

@@ -51,6 +51,9 @@ _sg_ws = _sig("insum_spmm_groupcoo_workspace_bytes", C.c_size_t, [_i64, _i64, _i
 _sg = _sig("insum_spmm_groupcoo", C.c_int,
            [_i64, _i64, _i64, _i64, _i32, _p, _p, _p, C.c_int, _p, _i64, C.c_int,
             _p, _i64, C.c_int, C.c_int, _p, C.c_size_t, _p])
+_sg_na = _sig("insum_spmm_groupcoo_noalloc", C.c_int,
+              [_i64, _i64, _i64, _i64, _i32, _p, _p, _p, C.c_int, _p, _i64, C.c_int,
+               _p, _i64, C.c_int, C.c_int, _p])
 _sb_ws = _sig("insum_spmm_blockgroupcoo_workspace_bytes", C.c_size_t,
               [_i64, _i64, _i64, _i32, _i32, _i32])
 _sb = _sig("insum_spmm_blockgroupcoo", C.c_int,
@@ -233,6 +236,19 @@ def insum_spmm_groupcoo(A: GroupCOO, B: torch.Tensor, C_out: torch.Tensor | None
              _ptr(B), B.stride(0), _DTYPE[B.dtype], _ptr(C_out), C_out.stride(0),
              _DTYPE[C_out.dtype], int(bool(accumulate)), _ptr(workspace), workspace.numel(), _stream())
     _check(st, "insum_spmm_groupcoo")
+    return C_out
+
+
+def insum_spmm_groupcoo_noalloc(A: GroupCOO, B: torch.Tensor, C_out: torch.Tensor,
+                                accumulate: bool = False) -> torch.Tensor:
+    """insum_spmm_groupcoo without a workspace; C_out is required (the call allocates nothing)."""
+    assert B.is_cuda and B.dim() == 2 and B.shape[0] == A.K and B.stride(1) == 1
+    N = B.shape[1]
+    assert C_out.is_cuda and C_out.dim() == 2 and C_out.shape == (A.M, N) and C_out.stride(1) == 1
+    st = _sg_na(A.M, A.K, N, A.G, A.g, _ptr(A.AM), _ptr(A.AK), _ptr(A.AV), _DTYPE[A.AV.dtype],
+                _ptr(B), B.stride(0), _DTYPE[B.dtype], _ptr(C_out), C_out.stride(0),
+                _DTYPE[C_out.dtype], int(bool(accumulate)), _stream())
+    _check(st, "insum_spmm_groupcoo_noalloc")
     return C_out
 
 

@@ -329,7 +329,8 @@ int next_pow2(int64_t x) {
 }
 
 // elem_size: bytes per element of B; vec: 16-byte path usable.
-Plan make_plan(int64_t N, int64_t G, int32_t g, int elem_size, bool vec) {
+// run_cap > 0 limits the number of runs (a caller with a fixed amount of scratch).
+Plan make_plan(int64_t N, int64_t G, int32_t g, int elem_size, bool vec, int64_t run_cap = 0) {
     Plan pl;
     pl.E = vec ? 16 / elem_size : 1;
     const int64_t chunks = ceil_div(N, pl.E);
@@ -342,7 +343,8 @@ Plan make_plan(int64_t N, int64_t G, int32_t g, int elem_size, bool vec) {
     // About two runs per sub-wave slot of the chip (256 CUs x 32 wavefronts), but never
     // fewer than two SW-slot batches per run.
     const int64_t subwaves = 256LL * 32 * (64 / pl.SW);
-    const int64_t target_runs = std::max<int64_t>(1, 2 * subwaves / pl.col_tiles);
+    int64_t target_runs = std::max<int64_t>(1, 2 * subwaves / pl.col_tiles);
+    if (run_cap > 0) target_runs = std::min(target_runs, run_cap);
     const int64_t min_groups = std::max<int64_t>(1, ceil_div(2 * pl.SW, g));
     pl.groups_per_run = std::max<int64_t>(min_groups, ceil_div(G, target_runs));
     pl.runs = G > 0 ? ceil_div(G, pl.groups_per_run) : 0;
@@ -389,22 +391,16 @@ extern "C" size_t insum_spmm_groupcoo_workspace_bytes(int64_t M, int64_t N, int6
     return align_up((size_t)runs * 2 * (size_t)padded_cols(N) * sizeof(float), 256) + 256;
 }
 
-extern "C" insum_status insum_spmm_groupcoo(int64_t M, int64_t K, int64_t N, int64_t G, int32_t g,
-                                            const int32_t* AM, const int32_t* AK, const void* AV,
-                                            insum_dtype a_dt, const void* B, int64_t ldb,
-                                            insum_dtype b_dt, void* C, int64_t ldc,
-                                            insum_dtype c_dt, int accumulate, void* workspace,
-                                            size_t workspace_bytes, void* stream) {
-    if (M < 0 || K < 0 || N < 0 || G < 0 || g <= 0) return INSUM_ERR_INVALID_ARG;
-    if (M >= (1LL << 31) || K >= (1LL << 31) || N >= (1LL << 31)) return INSUM_ERR_INVALID_ARG;
-    if (!dtype_valid(a_dt) || !dtype_valid(b_dt) || !dtype_valid(c_dt)) return INSUM_ERR_INVALID_ARG;
-    if (a_dt != b_dt || (c_dt != b_dt && c_dt != INSUM_F32)) return INSUM_ERR_UNSUPPORTED;
-    if (ldb < N || ldc < N) return INSUM_ERR_INVALID_ARG;
-    if (M == 0 || N == 0) return INSUM_OK;
-    if (!C) return INSUM_ERR_INVALID_ARG;
-    if (G > 0 && (!AM || !AK || !AV || !B || K == 0)) return INSUM_ERR_INVALID_ARG;
-    hipStream_t s = static_cast<hipStream_t>(stream);
+namespace insum {
+namespace {
 
+// Shared body of the two entry points.  `scratch` is 256-byte aligned device memory of
+// `scratch_bytes` bytes for the seam partials; run_cap as in make_plan.
+insum_status spmm_groupcoo_run(int64_t M, int64_t K, int64_t N, int64_t G, int32_t g,
+                               const int32_t* AM, const int32_t* AK, const void* AV, insum_dtype a_dt,
+                               const void* B, int64_t ldb, insum_dtype b_dt, void* C, int64_t ldc,
+                               insum_dtype c_dt, int accumulate, float* scratch, size_t scratch_bytes,
+                               int64_t run_cap, hipStream_t s) {
     if (G == 0) {
         if (!accumulate) {
             if (ceil_div(M * N, 256) >= (1LL << 31)) return INSUM_ERR_UNSUPPORTED;
@@ -421,7 +417,7 @@ extern "C" insum_status insum_spmm_groupcoo(int64_t M, int64_t K, int64_t N, int
     const bool vec = N % ev == 0 && ldb % ev == 0 && ldc % ev == 0 &&
                      (reinterpret_cast<uintptr_t>(B) % 16) == 0 &&
                      (reinterpret_cast<uintptr_t>(C) % 16) == 0;
-    const Plan pl = make_plan(N, G, g, es, vec);
+    const Plan pl = make_plan(N, G, g, es, vec, run_cap);
 
     GroupParams p;
     p.M = M; p.N = N; p.G = G; p.g = g;
@@ -433,10 +429,8 @@ extern "C" insum_status insum_spmm_groupcoo(int64_t M, int64_t K, int64_t N, int
     p.col_tiles = (int32_t)pl.col_tiles;
     if (ceil_div(pl.runs, 256 / pl.SW) * pl.col_tiles >= (1LL << 31)) return INSUM_ERR_UNSUPPORTED;
     const size_t need = (size_t)pl.runs * 2 * (size_t)p.npad * sizeof(float);
-    const uintptr_t ws = (reinterpret_cast<uintptr_t>(workspace) + 255) / 256 * 256;
-    if (!workspace || ws + need > reinterpret_cast<uintptr_t>(workspace) + workspace_bytes)
-        return INSUM_ERR_CAPACITY;
-    p.partial = reinterpret_cast<float*>(ws);
+    if (!scratch || need > scratch_bytes) return INSUM_ERR_CAPACITY;
+    p.partial = scratch;
 
     if (b_dt == INSUM_F32) launch_typed<float, float>(p, pl, s);
     else if (b_dt == INSUM_F16 && c_dt == INSUM_F16) launch_typed<__half, __half>(p, pl, s);
@@ -445,4 +439,98 @@ extern "C" insum_status insum_spmm_groupcoo(int64_t M, int64_t K, int64_t N, int
     else launch_typed<bf16_t, float>(p, pl, s);
     INSUM_HIP_TRY(hipGetLastError());
     return INSUM_OK;
+}
+
+insum_status check_spmm_groupcoo_args(int64_t M, int64_t K, int64_t N, int64_t G, int32_t g,
+                                      const int32_t* AM, const int32_t* AK, const void* AV, insum_dtype a_dt,
+                                      const void* B, int64_t ldb, insum_dtype b_dt, void* C, int64_t ldc,
+                                      insum_dtype c_dt, bool& nothing_to_do) {
+    nothing_to_do = false;
+    if (M < 0 || K < 0 || N < 0 || G < 0 || g <= 0) return INSUM_ERR_INVALID_ARG;
+    if (M >= (1LL << 31) || K >= (1LL << 31) || N >= (1LL << 31)) return INSUM_ERR_INVALID_ARG;
+    if (!dtype_valid(a_dt) || !dtype_valid(b_dt) || !dtype_valid(c_dt)) return INSUM_ERR_INVALID_ARG;
+    if (a_dt != b_dt || (c_dt != b_dt && c_dt != INSUM_F32)) return INSUM_ERR_UNSUPPORTED;
+    if (ldb < N || ldc < N) return INSUM_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) {
+        nothing_to_do = true;
+        return INSUM_OK;
+    }
+    if (!C) return INSUM_ERR_INVALID_ARG;
+    if (G > 0 && (!AM || !AK || !AV || !B || K == 0)) return INSUM_ERR_INVALID_ARG;
+    return INSUM_OK;
+}
+
+}  // namespace
+}  // namespace insum
+
+extern "C" insum_status insum_spmm_groupcoo(int64_t M, int64_t K, int64_t N, int64_t G, int32_t g,
+                                            const int32_t* AM, const int32_t* AK, const void* AV,
+                                            insum_dtype a_dt, const void* B, int64_t ldb,
+                                            insum_dtype b_dt, void* C, int64_t ldc,
+                                            insum_dtype c_dt, int accumulate, void* workspace,
+                                            size_t workspace_bytes, void* stream) {
+    bool done = false;
+    const insum_status st = check_spmm_groupcoo_args(M, K, N, G, g, AM, AK, AV, a_dt, B, ldb, b_dt, C, ldc, c_dt, done);
+    if (st != INSUM_OK || done) return st;
+    const uintptr_t base = reinterpret_cast<uintptr_t>(workspace);
+    const uintptr_t ws = (base + 255) / 256 * 256;
+    if (G > 0 && (!workspace || ws > base + workspace_bytes)) return INSUM_ERR_CAPACITY;
+    return spmm_groupcoo_run(M, K, N, G, g, AM, AK, AV, a_dt, B, ldb, b_dt, C, ldc, c_dt, accumulate,
+                             reinterpret_cast<float*>(ws), workspace ? base + workspace_bytes - ws : 0, 0,
+                             static_cast<hipStream_t>(stream));
+}
+
+// ---- entry point that allocates nothing ------------------------------------------------------
+// For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+// loops): the seam partials live in a file-scope device array instead of a caller workspace.
+// Every GPU the library runs on holds its own copy of the array until the process ends.
+namespace insum {
+namespace {
+
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];  // device address of `scratch`, per device; null until looked up
+
+// The array's name is only a host-side handle; its device address comes from the runtime, once
+// per device and with that device current.  Concurrent first calls may both look it up: they
+// obtain the same address.
+insum_status static_scratch(void** out) {
+    int dev = -1;
+    INSUM_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return INSUM_ERR_UNSUPPORTED;
+    void* ptr = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (!ptr) {
+        INSUM_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return INSUM_ERR_HIP;
+        __atomic_store_n(&g_scratch_ptr[dev], ptr, __ATOMIC_RELEASE);
+    }
+    *out = ptr;
+    return INSUM_OK;
+}
+
+}  // namespace
+}  // namespace insum
+
+extern "C" insum_status insum_spmm_groupcoo_noalloc(int64_t M, int64_t K, int64_t N, int64_t G, int32_t g,
+                                                    const int32_t* AM, const int32_t* AK, const void* AV,
+                                                    insum_dtype a_dt, const void* B, int64_t ldb,
+                                                    insum_dtype b_dt, void* C, int64_t ldc,
+                                                    insum_dtype c_dt, int accumulate, void* stream) {
+    bool done = false;
+    insum_status st = check_spmm_groupcoo_args(M, K, N, G, g, AM, AK, AV, a_dt, B, ldb, b_dt, C, ldc, c_dt, done);
+    if (st != INSUM_OK || done) return st;
+    // Each run stores a head piece and a tail piece of padded_cols(N) floats; a run is the least
+    // that can be scheduled, so a row of partials wider than the array cannot be served.
+    const size_t per_run = 2 * (size_t)padded_cols(N) * sizeof(float);
+    if (per_run > kStaticScratchBytes) return INSUM_ERR_CAPACITY;
+    void* ptr = nullptr;
+    st = static_scratch(&ptr);
+    if (st != INSUM_OK) return st;
+    // Every partial that the second kernel reads is written by the first kernel of the same
+    // call, so what an earlier call left in the array never has to be cleared.
+    return spmm_groupcoo_run(M, K, N, G, g, AM, AK, AV, a_dt, B, ldb, b_dt, C, ldc, c_dt, accumulate,
+                             static_cast<float*>(ptr), kStaticScratchBytes,
+                             (int64_t)(kStaticScratchBytes / per_run), static_cast<hipStream_t>(stream));
 }

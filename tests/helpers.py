@@ -89,16 +89,18 @@ def check_groupcoo_invariants(M, K, row, col, val, g, AM, AK, AV):
     assert np.all(flat_col[1:][same] >= flat_col[:-1][same])
 
 
-def assert_spmm_close(C_got, C64, absprod64, rtol, what=""):
+def assert_spmm_close(C_got, C64, absprod64, rtol, what="", out_dtype=None):
     """Parity criterion: max error relative to max|C| and a componentwise bound against
-    (|A| |B|), which does not suffer from cancellation."""
+    (|A| |B|), which does not suffer from cancellation.  A result stored as fp16 cannot be
+    closer to the exact value than half the spacing of fp16 subnormals (2^-25) wherever that
+    value is below the normal range, so out_dtype="f16" adds that much to the bound."""
     C_got = np.asarray(C_got, dtype=np.float64)
     E = np.abs(C_got - C64)
     scale = max(float(np.max(np.abs(C64))) if C64.size else 0.0, 1e-300)
     assert not np.any(np.isnan(C_got)), f"{what}: NaN in result"
     worst = float(E.max()) if E.size else 0.0
     assert worst <= rtol * scale, f"{what}: max err {worst:.3e} > {rtol} * {scale:.3e}"
-    bound = rtol * absprod64 + 1e-30
+    bound = rtol * absprod64 + (2.0 ** -25 if out_dtype == "f16" else 1e-30)
     bad = E > bound
     assert not bad.any(), (f"{what}: {int(bad.sum())} elements exceed the componentwise bound; "
                            f"worst ratio {float((E / bound).max()):.3f}")
