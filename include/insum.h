@@ -188,8 +188,25 @@ insum_status insum_spmm_groupcoo_noalloc(int64_t M, int64_t K, int64_t N, int64_
 /* SpMM over BlockGroupCOO (Section 4.1, BlockGroupCOO Einsum)                         */
 /* ---------------------------------------------------------------------------------- */
 
+/* Bytes of device workspace that hold a work plan (below) for these sizes; 0 for shapes that
+ * take no plan.  Host only. */
 size_t insum_spmm_blockgroupcoo_workspace_bytes(int64_t M, int64_t N, int64_t G, int32_t g,
                                                 int32_t bM, int32_t bK);
+
+/*
+ * Optional, once per matrix and dense width N: writes a work plan for insum_spmm_blockgroupcoo
+ * into `workspace` (device, at least insum_spmm_blockgroupcoo_workspace_bytes(...) bytes).
+ * The plan depends on AM only (which groups belong to which block row): it lists the block rows
+ * longest first - the order in which the matrix cores are kept busiest when block rows differ
+ * in length, as the fixed-length groups of Section 4.1 allow - and cuts a block row that is
+ * much longer than the mean load of a workgroup into chunks that are multiplied by different
+ * workgroups and added up in a fixed order.  A plan stays valid for every later SpMM call with
+ * the same M, N, G, g, bM, AM pointer and AM contents; it must be rebuilt when AM changes.
+ * Asynchronous; returns INSUM_OK without touching the workspace for shapes that take no plan.
+ */
+insum_status insum_spmm_blockgroupcoo_plan(int64_t M, int64_t K, int64_t N, int64_t G, int32_t g,
+                                           int32_t bM, int32_t bK, const int32_t* AM,
+                                           void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * C = A * B or C += A * B with A in BlockGroupCOO (layout as produced by
@@ -200,8 +217,18 @@ size_t insum_spmm_blockgroupcoo_workspace_bytes(int64_t M, int64_t N, int64_t G,
  *   of 32, N and ldb are multiples of 8, ldc is a multiple of 8 (4 for fp32 C) and B, AV, C
  *   are 16-byte aligned; other shapes, and a_dt == b_dt == F32, run on a slower general
  *   kernel with the same results up to summation order.
- *   A padding block (one that repeats the previous block column of its group) is
- *   skipped; B is assumed finite.
+ *   Among the real slots of a block row the block columns must be strictly increasing (as
+ *   insum_coo_to_blockgroupcoo produces them): a slot that repeats the block column of the
+ *   slot before it in its group is taken to be padding and is skipped whatever its values.
+ *   B is assumed finite.
+ *   workspace   NULL (workspace_bytes 0), or device memory of at least
+ *               insum_spmm_blockgroupcoo_workspace_bytes(...) bytes.  When it holds a plan made
+ *               by insum_spmm_blockgroupcoo_plan for the same M, N, G, g, bM and AM pointer the
+ *               call follows it (and uses the rest of the workspace for the partial tiles of
+ *               split block rows: calls that share a workspace must not overlap); contents
+ *               that are not such a plan are ignored and block rows are processed whole, in
+ *               index order.  Results with and without a plan agree up to fp32 summation
+ *               order, and each is reproducible from run to run.
  *
  * Other arguments and behaviour as for insum_spmm_groupcoo.  Asynchronous.
  */

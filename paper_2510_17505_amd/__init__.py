@@ -21,6 +21,7 @@ from .api import (  # noqa: F401
     insum_spconv_groupcoo,
     insum_spconv_groupcoo_workspace_bytes,
     insum_spmm_blockgroupcoo,
+    insum_spmm_blockgroupcoo_plan,
     insum_spmm_blockgroupcoo_workspace_bytes,
     insum_spmm_groupcoo,
     insum_spmm_groupcoo_noalloc,

@@ -3,7 +3,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
-from dataclasses import dataclass
+from dataclasses import dataclass, field
 
 import torch
 
@@ -59,6 +59,8 @@ _sb_ws = _sig("insum_spmm_blockgroupcoo_workspace_bytes", C.c_size_t,
 _sb = _sig("insum_spmm_blockgroupcoo", C.c_int,
            [_i64, _i64, _i64, _i64, _i32, _i32, _i32, _p, _p, _p, C.c_int, _p, _i64, C.c_int,
             _p, _i64, C.c_int, C.c_int, _p, C.c_size_t, _p])
+_sb_plan = _sig("insum_spmm_blockgroupcoo_plan", C.c_int,
+                [_i64, _i64, _i64, _i64, _i32, _i32, _i32, _p, _p, C.c_size_t, _p])
 _m_ws = _sig("insum_map_to_groupcoo_workspace_bytes", C.c_size_t, [_i64, _i64])
 _m_conv = _sig("insum_map_to_groupcoo", C.c_int,
                [_i64, _i64, _i64, _i64, _p, _p, _p, _p, C.c_int, _i32, _p, _p, _p, _p, _p, _p, _i64,
@@ -138,6 +140,7 @@ class BlockGroupCOO:
     AM: torch.Tensor   # int32 [G]          block rows
     AK: torch.Tensor   # int32 [G, g]       block columns
     AV: torch.Tensor   # dtype [G, g, bM, bK]
+    plans: dict = field(default_factory=dict, repr=False)   # N -> planned workspace (see insum_spmm_blockgroupcoo_plan)
 
     @property
     def G(self) -> int:
@@ -252,15 +255,31 @@ def insum_spmm_groupcoo_noalloc(A: GroupCOO, B: torch.Tensor, C_out: torch.Tenso
     return C_out
 
 
+def insum_spmm_blockgroupcoo_plan(A: BlockGroupCOO, N: int) -> torch.Tensor | None:
+    """Builds the work plan of A for dense width N in a fresh workspace and returns it (None for
+    shapes that take no plan).  The plan stays valid while A.AM is unchanged."""
+    nws = insum_spmm_blockgroupcoo_workspace_bytes(A.M, N, A.G, A.g, A.bM, A.bK)
+    if nws == 0:
+        return None
+    ws = torch.empty(nws, dtype=torch.uint8, device=A.AM.device)
+    _check(_sb_plan(A.M, A.K, N, A.G, A.g, A.bM, A.bK, _ptr(A.AM), _ptr(ws), ws.numel(), _stream()),
+           "insum_spmm_blockgroupcoo_plan")
+    return ws
+
+
 def insum_spmm_blockgroupcoo(A: BlockGroupCOO, B: torch.Tensor, C_out: torch.Tensor | None = None,
-                             accumulate: bool = False, out_dtype=None, workspace=None) -> torch.Tensor:
-    """C = A @ B (or C += A @ B) with A in BlockGroupCOO."""
+                             accumulate: bool = False, out_dtype=None, workspace=None,
+                             plan: bool = True) -> torch.Tensor:
+    """C = A @ B (or C += A @ B) with A in BlockGroupCOO.  `workspace`: a planned workspace from
+    insum_spmm_blockgroupcoo_plan; when it is None and `plan` is true, the plan for this N is
+    built on first use and kept in A.plans; plan=False passes no workspace at all."""
     assert B.is_cuda and B.dim() == 2 and B.shape[0] == A.K and B.stride(1) == 1
     N = B.shape[1]
     C_out = _out(C_out, A.M, N, out_dtype or B.dtype, B.device, accumulate)
-    nws = insum_spmm_blockgroupcoo_workspace_bytes(A.M, N, A.G, A.g, A.bM, A.bK)
-    if workspace is None and nws:
-        workspace = torch.empty(nws, dtype=torch.uint8, device=B.device)
+    if workspace is None and plan and A.G:
+        if N not in A.plans:
+            A.plans[N] = insum_spmm_blockgroupcoo_plan(A, N)
+        workspace = A.plans[N]
     st = _sb(A.M, A.K, N, A.G, A.g, A.bM, A.bK, _ptr(A.AM), _ptr(A.AK), _ptr(A.AV),
              _DTYPE[A.AV.dtype], _ptr(B), B.stride(0), _DTYPE[B.dtype], _ptr(C_out),
              C_out.stride(0), _DTYPE[C_out.dtype], int(bool(accumulate)), _ptr(workspace),

@@ -325,6 +325,77 @@ def test_spmm_blockgroupcoo_accumulate_and_f32_out(I, bM, bK, N):
     assert_spmm_close(Cf.cpu().numpy(), C64b, absb, RTOL[dtype], "f32 out")
 
 
+def _hub_block_coo(nbr, nbc, bM, bK, occ, seed, dtype):
+    """Block rows with the given numbers of blocks, block columns uniform without repetition."""
+    rng = np.random.default_rng(seed)
+    rows, cols = [], []
+    for r, k in enumerate(occ):
+        bc = np.sort(rng.choice(nbc, size=int(k), replace=False))
+        rr = (r * bM + np.arange(bM))[None, :, None] + np.zeros((int(k), 1, bK), np.int64)
+        cc = (bc[:, None, None] * bK + np.arange(bK)[None, None, :]) + np.zeros((1, bM, 1), np.int64)
+        rows.append(rr.reshape(-1))
+        cols.append(cc.reshape(-1))
+    row = np.concatenate(rows).astype(np.int32)
+    col = np.concatenate(cols).astype(np.int32)
+    val = synth.round_to_dtype(rng.standard_normal(row.size) * 0.5, dtype)
+    perm = rng.permutation(row.size)
+    return row[perm], col[perm], val[perm]
+
+
+@pytest.mark.parametrize("bM,bK,N,g,dtype,out32,accumulate", [
+    (32, 32, 264, 3, "bf16", False, False),    # ragged column tile, g not a power of two
+    (64, 64, 512, 4, "f16", True, True),       # fp32 C, accumulating: only the last chunk adds the old C
+])
+def test_spmm_blockgroupcoo_hub_block_row_is_split_by_the_plan(I, bM, bK, N, g, dtype, out32, accumulate):
+    """One block row holds more than 2 000 blocks: the plan cuts it into chunks that different
+    workgroups multiply; their fp32 tiles are added in a fixed order.  Checked against the
+    oracle with and without the plan, and on repeated calls that reuse the plan."""
+    nbr, nbc = 6, 2300
+    occ = [3, 2100, 0, 40, 1, 700]
+    M, K = nbr * bM, nbc * bK
+    row, col, val = _hub_block_coo(nbr, nbc, bM, bK, occ, seed=bM + N, dtype=dtype)
+    _say(f"[spmm blockgroupcoo hub] b={bM}x{bK} N={N} g={g} {dtype} nnz={row.size}")
+    fmt = oracle.coo_to_blockgroupcoo(M, K, row, col, synth.storage_array(val, dtype), bM, bK, g)
+    B = synth.round_to_dtype(np.random.default_rng(N).standard_normal((K, N)), dtype)
+    C0 = synth.round_to_dtype(np.random.default_rng(1).standard_normal((M, N)), "f32" if out32 else dtype)
+    C64, absprod = _oracle_block_spmm(M, K, N, bM, bK, fmt, dtype, B, C0.astype(np.float64) if accumulate else None)
+    A = _gpu_block_format(I, M, K, bM, bK, fmt, dtype)
+    Bd = values_to_torch(B, dtype)
+    odt = torch.float32 if out32 else TORCH_DTYPE[dtype]
+
+    def run(**kw):
+        C = values_to_torch(C0, "f32" if out32 else dtype)
+        I.insum_spmm_blockgroupcoo(A, Bd, C_out=C, accumulate=accumulate, **kw)
+        assert C.dtype == odt
+        return C
+
+    ws = I.insum_spmm_blockgroupcoo_plan(A, N)
+    assert ws is not None
+    planned = run(workspace=ws)
+    assert_spmm_close(planned.float().cpu().numpy(), C64, absprod, RTOL[dtype], "planned")
+    for _ in range(3):                      # the plan (and its arrival counters) serve later calls unchanged
+        assert torch.equal(planned, run(workspace=ws))
+    unplanned = run(plan=False)
+    assert_spmm_close(unplanned.float().cpu().numpy(), C64, absprod, RTOL[dtype], "no workspace")
+    junk = torch.randint(0, 255, (ws.numel(),), dtype=torch.uint8, device="cuda")
+    assert torch.equal(unplanned, run(workspace=junk))       # not a plan: ignored
+    other = I.insum_spmm_blockgroupcoo_plan(A, N)            # a second plan of the same matrix
+    assert torch.equal(planned, run(workspace=other))
+
+
+def test_spmm_blockgroupcoo_plan_orders_rows_without_changing_results(I):
+    """Zipf block rows, none long enough to be split: with a plan the block rows are issued
+    longest first, each still summed by one workgroup in the same order -> identical bits."""
+    M = K = 4096
+    N, bM, bK, g = 1024, 64, 64, 4
+    row, col, val = synth.random_block_coo(M, K, bM, bK, seed=3, dtype="bf16", zipf_alpha=1.0,
+                                           zipf_mean=6.0, sigma=0.5)
+    A = I.insum_coo_to_blockgroupcoo(M, K, *coo_to_device(row, col, val, "bf16"), bM, bK, g=g)
+    Bd = values_to_torch(synth.round_to_dtype(np.random.default_rng(0).standard_normal((K, N)), "bf16"), "bf16")
+    assert torch.equal(I.insum_spmm_blockgroupcoo(A, Bd), I.insum_spmm_blockgroupcoo(A, Bd, plan=False))
+    assert N in A.plans
+
+
 # --------------------------------------------------------------------------- #
 # robustness
 # --------------------------------------------------------------------------- #

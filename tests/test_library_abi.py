@@ -63,7 +63,8 @@ def test_argument_validation_without_a_gpu():
     assert call(4, 4, 4, 1, 2, 0, 0, 0, 0, 0, 4, 0, 0, 4, 0, 0, 0, 0, 0) == 1     # null C
     assert call(0, 4, 4, 0, 2, 0, 0, 0, 0, 0, 4, 0, 0, 4, 0, 0, 0, 0, 0) == 0     # empty problem
     assert I.insum_spmm_groupcoo_workspace_bytes(1 << 20, 128, 4_600_000, 4) > 0
-    assert I.insum_spmm_blockgroupcoo_workspace_bytes(8192, 512, 1760, 4, 32, 32) == 0
+    assert I.insum_spmm_blockgroupcoo_workspace_bytes(8192, 512, 1760, 4, 32, 32) > 0    # room for a plan
+    assert I.insum_spmm_blockgroupcoo_workspace_bytes(8192, 512, 1760, 4, 8, 8) == 0      # general kernel: none
 
 
 def test_conversion_argument_validation_without_a_gpu():
