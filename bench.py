@@ -113,22 +113,67 @@ def prepare(torch, I, name):
     return cfg, A, B, nnz, conv_ms
 
 
-def run_workload(torch, I, name, steps, warmup):
+def _kernel_source_hashes():
+    """sha256 of the kernel sources, by file name: a stored counter figure is only quoted for the
+    sources it was measured on."""
+    import hashlib
+    out = {}
+    csrc = os.path.join(ROOT, "paper_2510_17505_amd", "csrc")
+    for fn in sorted(os.listdir(csrc)):
+        with open(os.path.join(csrc, fn), "rb") as f:
+            out[fn] = hashlib.sha256(f.read()).hexdigest()
+    return out
+
+
+def _traffic(name):
+    """Counter-measured bytes per launch between L2 and the memory fabric (FETCH_SIZE + WRITE_SIZE,
+    rocprofv3) from profiles/hbm_traffic.json, or None when that figure was taken on other kernel
+    sources than the ones in the tree."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            entry = json.load(f).get(name)
+    except (OSError, ValueError):
+        return None
+    if not entry:
+        return None
+    now = _kernel_source_hashes()
+    for fn, sha in entry.get("source_sha256", {"?": "?"}).items():
+        if now.get(fn) != sha:
+            return None
+    return entry.get("hbm_bytes_per_launch")
+
+
+def run_workload(torch, I, name, steps, warmup, peaks=None):
     cfg, A, B, nnz, conv_ms = prepare(torch, I, name)
     M, N = cfg["M"], cfg["N"]
     sA, sB, sC = SIZEOF[cfg["a_dtype"]], SIZEOF[cfg["b_dtype"]], SIZEOF[cfg["c_dtype"]]
     C = torch.empty((M, N), dtype=_torch_dtype(torch, cfg["c_dtype"]), device="cuda")
+    plan_ms = None
     if cfg["kind"] == "group":
         ws = torch.empty(I.insum_spmm_groupcoo_workspace_bytes(M, N, A.G, A.g), dtype=torch.uint8,
                          device="cuda")
         fn = lambda: I.insum_spmm_groupcoo(A, B, C_out=C, workspace=ws)
         slots = A.G * A.g
+        # Bytes that have to come from beyond the caches when B does not fit them: every real
+        # entry gathers a row of B; a padding slot repeats the row just fetched and adds only
+        # its own column index and value; AM, and C written once.
+        real_bytes = nnz * (N * sB + 4 + sA) + (slots - nnz) * (4 + sA) + 4 * A.G + M * N * sC
+        # The same with every slot counted as a gather (what the kernel requests from L1/L2).
         model_bytes = slots * (N * sB + 4 + sA) + 4 * A.G + M * N * sC
         stored = slots
     else:
+        for _ in range(2):                      # once per matrix and N, like the conversion
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            plan = I.insum_spmm_blockgroupcoo_plan(A, N)
+            torch.cuda.synchronize()
+            plan_ms = (time.perf_counter() - t0) * 1e3
+        A.plans[N] = plan
         fn = lambda: I.insum_spmm_blockgroupcoo(A, B, C_out=C)
         nblk = nnz // (cfg["bM"] * cfg["bK"])
         model_bytes = nblk * (cfg["bM"] * cfg["bK"] * sA + cfg["bK"] * N * sB) + 8 * A.G * A.g + M * N * sC
+        real_bytes = model_bytes
         stored = nblk
     ms = _time_launches(torch, fn, steps, warmup)
     flops = 2.0 * nnz * N
@@ -139,18 +184,56 @@ def run_workload(torch, I, name, steps, warmup):
         "model_bytes": int(model_bytes), "model_gbs": model_bytes / ms / 1e6,
         "conversion_ms": conv_ms,
     }
+    if plan_ms is not None:
+        res["plan_ms"] = plan_ms
+    b_bytes = cfg["K"] * N * sB
     if cfg["kind"] == "group":
-        res["roofline"] = {"bound": "hbm", "achieved": res["model_gbs"], "peak": HBM_PEAK_GBS,
-                           "unit": "GB/s", "frac": res["model_gbs"] / HBM_PEAK_GBS,
-                           "traffic": _traffic(name)}
-        if cfg["K"] * N * sB <= (32 << 20):
-            res["roofline"]["note"] = ("B fits the 8 x 4 MiB L2: the gathers are served by the caches, "
-                                       "so algorithmic GB/s can exceed the HBM peak and HBM is not what "
-                                       "bounds this workload")
+        gbs = real_bytes / ms / 1e6
+        roof = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": gbs / HBM_PEAK_GBS, "traffic": _traffic(name),
+                "bytes_per_launch": int(real_bytes),
+                "bytes_rule": "nnz*(N*sB+4+sA) + padding_slots*(4+sA) + 4*G + M*N*sC (a padding slot's "
+                              "gather repeats the row just fetched and is not counted)"}
+        if peaks:
+            row_bytes = N * sB
+            key = "2GiB" if b_bytes > (256 << 20) else "128MiB" if b_bytes > (32 << 20) else None
+            mp = peaks.get("random_row_read_gbs", {}).get(str(row_bytes), {}).get(key) if key else None
+            if mp:
+                roof["measured_peak"] = mp
+                roof["frac_of_measured_peak"] = gbs / mp
+                roof["measured_peak_is"] = (f"random {row_bytes}-byte row reads over a {key} set "
+                                            f"(csrc/peaks.hip), the access pattern of the gather")
+            roof["frac_of_bound"] = gbs / HBM_PEAK_GBS      # min(HBM, ALU) = HBM for a 0.5 flop/byte path
+        if b_bytes <= (32 << 20):
+            roof["note"] = ("B fits the 8 x 4 MiB L2: the gathers are served by the caches; bytes are "
+                            "counted as if they came from memory, so this figure can exceed the HBM "
+                            "peak and HBM is not what bounds this workload")
+        elif b_bytes <= (256 << 20):
+            roof["note"] = ("B fits the 256 MB Infinity Cache: most of these bytes cross the fabric "
+                            "between L2 and that cache, not the HBM interface")
+        else:
+            roof["note"] = (f"B is {b_bytes >> 20} MiB against a 256 MB Infinity Cache: up to "
+                            f"{min(1.0, 256e6 / b_bytes):.2f} of the gathers can still be served by that "
+                            f"cache rather than by HBM itself; `traffic` counts both")
+        res["roofline"] = roof
     else:
         tf = flops / ms / 1e9
-        res["roofline"] = {"bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS,
-                           "unit": "TFLOP/s", "frac": tf / MFMA_PEAK_TFLOPS, "traffic": _traffic(name)}
+        roof = {"bound": "mfma", "achieved": tf, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": tf / MFMA_PEAK_TFLOPS, "traffic": _traffic(name)}
+        if peaks:
+            # The format fixes bM flop per gathered byte of B (a gathered tile serves the bM rows of
+            # one block); B tiles that miss L2 arrive at the measured rate of L2-missing reads.
+            beyond_l2 = peaks.get("random_1kib_read_gbs", {}).get("128MiB")
+            if beyond_l2:
+                bound = min(MFMA_PEAK_TFLOPS, cfg["bM"] * beyond_l2 / 1e3)
+                roof["bound_tflops"] = bound
+                roof["bound_is"] = (f"min(MFMA peak, bM = {cfg['bM']} flop/byte x {beyond_l2:.0f} GB/s of "
+                                    f"L2-missing 1 KiB reads measured on this chip)")
+                roof["frac_of_bound"] = tf / bound
+            if peaks.get("mfma_bf16_tflops"):
+                roof["measured_peak"] = peaks["mfma_bf16_tflops"]
+                roof["frac_of_measured_peak"] = tf / peaks["mfma_bf16_tflops"]
+        res["roofline"] = roof
     return res, (cfg, A, B, C)
 
 
@@ -206,33 +289,29 @@ def run_spconv(torch, I, steps, warmup):
                                  "reads, not by HBM or the matrix cores"}}
 
 
-def _traffic(name):
-    """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    try:
-        with open(path) as f:
-            return json.load(f).get(name, {}).get("hbm_bytes_per_launch")
-    except (OSError, ValueError):
-        return None
-
-
 def measured_peaks():
     """Achievable rates of this chip from the library's microbenchmarks (context for the
-    datasheet peaks the roofline fractions use)."""
+    datasheet peaks, and the denominators of frac_of_measured_peak / frac_of_bound)."""
     import ctypes
     from paper_2510_17505_amd import _build
     lib = ctypes.CDLL(_build.PEAKS_LIB)
     for name, args in (("insum_peak_copy_gbs", [ctypes.c_size_t, ctypes.c_int]),
+                       ("insum_peak_read_gbs", [ctypes.c_size_t, ctypes.c_int]),
                        ("insum_peak_random_read_gbs", [ctypes.c_size_t, ctypes.c_int]),
+                       ("insum_peak_random_rows_gbs", [ctypes.c_size_t, ctypes.c_int, ctypes.c_int]),
                        ("insum_peak_mfma_tflops", [ctypes.c_int])):
         getattr(lib, name).restype = ctypes.c_double
         getattr(lib, name).argtypes = args
+    sets = (("128MiB", 128 << 20), ("2GiB", 2 << 30))
     return {
-        "stream_copy_gbs": lib.insum_peak_copy_gbs(1 << 30, 3),
+        "stream_copy_gbs": lib.insum_peak_copy_gbs(2 << 30, 3),
+        "stream_read_gbs": lib.insum_peak_read_gbs(2 << 30, 3),
         "random_1kib_read_gbs": {"1MiB": lib.insum_peak_random_read_gbs(1 << 20, 2),
                                  "16MiB": lib.insum_peak_random_read_gbs(16 << 20, 2),
                                  "128MiB": lib.insum_peak_random_read_gbs(128 << 20, 2),
                                  "2GiB": lib.insum_peak_random_read_gbs(2 << 30, 2)},
+        "random_row_read_gbs": {str(rb): {k: lib.insum_peak_random_rows_gbs(ws, rb, 2) for k, ws in sets}
+                                for rb in (256, 512)},
         "mfma_bf16_tflops": lib.insum_peak_mfma_tflops(2),
     }
 
@@ -388,6 +467,8 @@ def main():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--no-extra", action="store_true", help="skip the other configs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-peaks", action="store_true",
+                    help="skip the achievable-peak microbenchmarks (and the fractions that use them)")
     ap.add_argument("--sweep", action="store_true",
                     help="only run the group-size sweep on the paper's ablation shape")
     ap.add_argument("--context", action="store_true",
@@ -435,7 +516,8 @@ def main():
     if args.sweep:
         print(json.dumps({"group_size_sweep": group_size_sweep(torch, I, args.steps, args.warmup)}))
         return
-    res, (cfg, A, B, C) = run_workload(torch, I, args.workload, args.steps, args.warmup)
+    peaks = None if args.no_peaks else measured_peaks()
+    res, (cfg, A, B, C) = run_workload(torch, I, args.workload, args.steps, args.warmup, peaks)
     line = {
         "metric": "SpMM GFLOP/s (2*nnz*N)", "value": res["gflops"], "unit": "GFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
@@ -446,8 +528,11 @@ def main():
                    "format": res["format"], "g": res["g"], "groups": res["groups"]},
         "roofline": res["roofline"],
         "model_bytes_per_launch": res["model_bytes"],
+        "model_gbs": res["model_gbs"],
         "conversion_ms": res["conversion_ms"],
     }
+    if "plan_ms" in res:
+        line["plan_ms"] = res["plan_ms"]
     if cfg["kind"] == "group":
         ws = torch.empty(I.insum_spmm_groupcoo_workspace_bytes(cfg["M"], cfg["N"], A.G, A.g), dtype=torch.uint8,
                          device="cuda")
@@ -465,14 +550,15 @@ def main():
         for name in ("cfg3_f16", "cfg5", "cfg4", "cfg2", "cfg1"):
             if name == args.workload:
                 continue
-            r, keep = run_workload(torch, I, name, args.steps, args.warmup)
+            r, keep = run_workload(torch, I, name, args.steps, args.warmup, peaks)
             del keep
             torch.cuda.empty_cache()
             others[name] = {k: r[k] for k in ("format", "dtype", "nnz", "N", "g", "ms_per_step", "gflops",
-                                              "model_gbs", "roofline", "conversion_ms")}
+                                              "model_gbs", "roofline", "conversion_ms", "plan_ms") if k in r}
         others["spconv"] = run_spconv(torch, I, args.steps, args.warmup)
         line["other_workloads"] = others
-        line["measured_peaks"] = measured_peaks()
+    if peaks is not None:
+        line["measured_peaks"] = peaks
     print(json.dumps(line))
 
 

@@ -19,16 +19,15 @@
 // way: key = z*X + x, the sort carries (y, value bits) packed in 64 bits, and the offsets play
 // the part of the rows.
 //
-// The device-wide sort and prefix sums are rocPRIM's (library primitives); everything
-// specific to the formats is in the kernels of this file.
+// The device-wide stable radix sort and the prefix sums are in sort_scan.h; keys are 32 bits
+// wide when the largest possible key fits (it does for every block workload here) and 64 bits
+// otherwise, and only the digits such a key can have are sorted.
 #include <cstring>
-
-#include <rocprim/device/device_radix_sort.hpp>
-#include <rocprim/device/device_scan.hpp>
 
 #include <algorithm>
 
 #include "common.h"
+#include "sort_scan.h"
 
 namespace insum {
 namespace {
@@ -50,6 +49,8 @@ struct Divisor {
     int32_t shift;  // log2(d) or -1
     explicit Divisor(uint64_t v) : d(v), shift((v & (v - 1)) == 0 ? __builtin_ctzll(v) : -1) {}
     __device__ uint64_t div(uint64_t x) const { return shift >= 0 ? (x >> shift) : (x / d); }
+    // 32-bit keys: same quotient with 32-bit arithmetic (d fits whenever the key does)
+    __device__ uint32_t div(uint32_t x) const { return shift >= 0 ? (x >> shift) : (x / (uint32_t)d); }
 };
 
 // ---- workspace carving -------------------------------------------------------------------
@@ -74,27 +75,6 @@ struct Carver {
     }
 };
 
-template <typename V>
-size_t sort_temp_bytes_v(int64_t nnz) {
-    size_t bytes = 0;
-    uint64_t* k = nullptr;
-    V* v = nullptr;
-    (void)rocprim::radix_sort_pairs(nullptr, bytes, k, k, v, v, (size_t)std::max<int64_t>(nnz, 1), 0, 64);
-    return bytes;
-}
-size_t sort_temp_bytes(int64_t nnz) {
-    return std::max(sort_temp_bytes_v<uint32_t>(nnz), sort_temp_bytes_v<uint16_t>(nnz));
-}
-size_t sort_temp_bytes_map(int64_t nnz) { return sort_temp_bytes_v<uint64_t>(nnz); }
-
-size_t scan_temp_bytes(int64_t n) {
-    size_t bytes = 0;
-    int32_t* x = nullptr;
-    (void)rocprim::exclusive_scan(nullptr, bytes, x, x, 0, (size_t)std::max<int64_t>(n, 1),
-                                  rocprim::plus<int32_t>());
-    return bytes;
-}
-
 struct Flags {  // device-side status words, copied to the host with the counts
     int32_t out_of_range;
     int32_t duplicate;
@@ -110,8 +90,9 @@ __global__ void k_zero_i32(int32_t* p, int64_t n) {
 
 // start[r] = index of the first sorted entry whose row (key / per_row) is >= r, for r in
 // [0, nrows]; start[nrows] = nnz.  Thread i owns the rows in (row(i-1), row(i)].
+template <typename KeyT>
 __global__ void k_row_bounds(int64_t nnz, int64_t nrows, Divisor per_row,
-                             const uint64_t* __restrict__ key, int32_t* __restrict__ start) {
+                             const KeyT* __restrict__ key, int32_t* __restrict__ start) {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i > nnz) return;
     const int64_t cur = i < nnz ? (int64_t)per_row.div(key[i]) : nrows;
@@ -144,9 +125,9 @@ __global__ void k_fill_zero(V* p, int64_t n) {
 }
 
 // ---- kernels: GroupCOO ---------------------------------------------------------------------
-template <bool HISTOGRAM>
+template <typename KeyT, bool HISTOGRAM>
 __global__ void k_group_keys(int64_t M, int64_t K, int64_t nnz, const int32_t* __restrict__ row,
-                             const int32_t* __restrict__ col, uint64_t* __restrict__ key,
+                             const int32_t* __restrict__ col, KeyT* __restrict__ key,
                              int32_t* __restrict__ occ, Flags* flags) {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= nnz) return;
@@ -156,20 +137,20 @@ __global__ void k_group_keys(int64_t M, int64_t K, int64_t nnz, const int32_t* _
     if constexpr (HISTOGRAM) {
         if (ok) atomicAdd(&occ[r], 1);
     } else {
-        key[i] = ok ? (uint64_t)r * (uint64_t)K + (uint64_t)c : 0;
+        key[i] = ok ? (KeyT)((uint64_t)r * (uint64_t)K + (uint64_t)c) : (KeyT)0;
     }
 }
 
-template <typename V>
-__global__ void k_group_fill(Divisor per_row, int64_t nnz, int32_t g, const uint64_t* __restrict__ key,
+template <typename KeyT, typename V>
+__global__ void k_group_fill(Divisor per_row, int64_t nnz, int32_t g, const KeyT* __restrict__ key,
                              const V* __restrict__ val, const int32_t* __restrict__ row_start,
                              const int32_t* __restrict__ grp_start, int32_t* __restrict__ AM,
                              int32_t* __restrict__ AK, V* __restrict__ AV) {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= nnz) return;
-    const uint64_t k = key[i];
+    const KeyT k = key[i];
     const int64_t r = (int64_t)per_row.div(k);
-    const int32_t c = (int32_t)(k - (uint64_t)r * per_row.d);
+    const int32_t c = (int32_t)((uint64_t)k - (uint64_t)r * per_row.d);
     const int32_t first = row_start[r];
     const int32_t rank = (int32_t)(i - first);
     const int32_t occ = row_start[r + 1] - first;
@@ -188,9 +169,10 @@ __global__ void k_group_fill(Divisor per_row, int64_t nnz, int32_t g, const uint
 }
 
 // ---- kernels: BlockGroupCOO ----------------------------------------------------------------
+template <typename KeyT>
 __global__ void k_block_keys(int64_t M, int64_t K, int64_t nnz, int32_t bM, int32_t bK,
                              const int32_t* __restrict__ row, const int32_t* __restrict__ col,
-                             uint64_t* __restrict__ key, Flags* flags) {
+                             KeyT* __restrict__ key, Flags* flags) {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= nnz) return;
     const int32_t r = row[i], c = col[i];
@@ -201,14 +183,15 @@ __global__ void k_block_keys(int64_t M, int64_t K, int64_t nnz, int32_t bM, int3
     }
     const uint64_t nbc = (uint64_t)(K / bK);
     const uint64_t blk = (uint64_t)(r / bM) * nbc + (uint64_t)(c / bK);
-    key[i] = (blk * (uint64_t)bM + (uint64_t)(r % bM)) * (uint64_t)bK + (uint64_t)(c % bK);
+    key[i] = (KeyT)((blk * (uint64_t)bM + (uint64_t)(r % bM)) * (uint64_t)bK + (uint64_t)(c % bK));
 }
 
 // On sorted keys: head[i] = 1 when entry i is the first of its block; counts blocks per
 // block row; equal neighbouring keys are duplicate coordinates.  head has nnz+1 entries
 // (the last is 0) so its exclusive scan ends with the number of blocks.
+template <typename KeyT>
 __global__ void k_block_heads(int64_t nnz, Divisor per_block, Divisor blocks_per_row,
-                              const uint64_t* __restrict__ key, int32_t* __restrict__ head,
+                              const KeyT* __restrict__ key, int32_t* __restrict__ head,
                               int32_t* __restrict__ occ, Flags* flags) {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i > nnz) return;
@@ -219,7 +202,7 @@ __global__ void k_block_heads(int64_t nnz, Divisor per_block, Divisor blocks_per
     const uint64_t blk = per_block.div(key[i]);
     int32_t h = 1;
     if (i > 0) {
-        const uint64_t prev = key[i - 1];
+        const KeyT prev = key[i - 1];
         if (prev == key[i]) flags->duplicate = 1;
         h = per_block.div(prev) != blk;
     }
@@ -227,9 +210,9 @@ __global__ void k_block_heads(int64_t nnz, Divisor per_block, Divisor blocks_per
     if (h) atomicAdd(&occ[blocks_per_row.div(blk)], 1);
 }
 
-template <typename V>
+template <typename KeyT, typename V>
 __global__ void k_block_fill(Divisor per_block, Divisor blocks_per_row, int64_t nnz, int32_t g,
-                             const uint64_t* __restrict__ key, const V* __restrict__ val,
+                             const KeyT* __restrict__ key, const V* __restrict__ val,
                              const int32_t* __restrict__ head, const int32_t* __restrict__ blk_ord,
                              const int32_t* __restrict__ brow_start,
                              const int32_t* __restrict__ grp_start, int32_t* __restrict__ AM,
@@ -264,10 +247,10 @@ constexpr int kLdsBins = 4096;  // offsets counted in LDS when Z is at most this
 // Validates the coordinates.  Fill mode forms key = z*X + x and payload = (y << 32) | value
 // bits.  Count mode adds to occ[z]: per work-group in LDS first when Z <= kLdsBins (a stencil
 // has few offsets, so global atomics would all hit the same few words).
-template <typename V, bool HISTOGRAM>
+template <typename KeyT, typename V, bool HISTOGRAM>
 __global__ void k_map_keys(int64_t X, int64_t Y, int64_t Z, int64_t nnz, const int32_t* __restrict__ mx,
                            const int32_t* __restrict__ my, const int32_t* __restrict__ mz,
-                           const V* __restrict__ mv, uint64_t* __restrict__ key,
+                           const V* __restrict__ mv, KeyT* __restrict__ key,
                            uint64_t* __restrict__ payload, int32_t* __restrict__ occ, Flags* flags) {
     __shared__ int32_t bins[HISTOGRAM ? kLdsBins : 1];
     const bool lds = HISTOGRAM && Z <= kLdsBins;
@@ -285,7 +268,7 @@ __global__ void k_map_keys(int64_t X, int64_t Y, int64_t Z, int64_t nnz, const i
         if constexpr (HISTOGRAM) {
             if (ok) atomicAdd(lds ? &bins[z] : &occ[z], 1);
         } else {
-            key[i] = ok ? (uint64_t)z * (uint64_t)X + (uint64_t)x : 0;
+            key[i] = ok ? (KeyT)((uint64_t)z * (uint64_t)X + (uint64_t)x) : (KeyT)0;
             payload[i] = ((uint64_t)(uint32_t)y << 32) | (uint64_t)mv[i];
         }
     }
@@ -298,17 +281,17 @@ __global__ void k_map_keys(int64_t X, int64_t Y, int64_t Z, int64_t nnz, const i
     }
 }
 
-template <typename V>
-__global__ void k_map_fill(Divisor per_z, int64_t nnz, int32_t g, const uint64_t* __restrict__ key,
+template <typename KeyT, typename V>
+__global__ void k_map_fill(Divisor per_z, int64_t nnz, int32_t g, const KeyT* __restrict__ key,
                            const uint64_t* __restrict__ payload, const int32_t* __restrict__ z_start,
                            const int32_t* __restrict__ grp_start, int32_t* __restrict__ MAPZ,
                            int32_t* __restrict__ MAPX, int32_t* __restrict__ MAPY, V* __restrict__ MAPV) {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= nnz) return;
-    const uint64_t k = key[i];
+    const KeyT k = key[i];
     const uint64_t pl = payload[i];
     const int64_t z = (int64_t)per_z.div(k);
-    const int32_t x = (int32_t)(k - (uint64_t)z * per_z.d);
+    const int32_t x = (int32_t)((uint64_t)k - (uint64_t)z * per_z.d);
     const int32_t y = (int32_t)(pl >> 32);
     const int32_t first = z_start[z];
     const int32_t rank = (int32_t)(i - first);
@@ -330,30 +313,259 @@ __global__ void k_map_fill(Divisor per_z, int64_t nnz, int32_t g, const uint64_t
 }
 
 // ---- host helpers ---------------------------------------------------------------------------
-template <typename T>
-insum_status scan_exclusive(void* temp, size_t temp_bytes, const T* in, T* out, int64_t n,
+insum_status scan_exclusive(void* temp, size_t temp_bytes, const int32_t* in, int32_t* out, int64_t n,
                             hipStream_t s) {
-    INSUM_HIP_TRY(rocprim::exclusive_scan(temp, temp_bytes, in, out, (T)0, (size_t)n,
-                                          rocprim::plus<T>(), s));
-    return INSUM_OK;
+    return exclusive_scan_i32(temp, temp_bytes, in, out, n, s);
 }
 
-template <typename V>
-insum_status sort_by_key(void* temp, size_t temp_bytes, const uint64_t* key_in, uint64_t* key_out,
-                         const void* val_in, void* val_out, int64_t nnz, int key_bits, hipStream_t s) {
-    size_t need = 0;
-    INSUM_HIP_TRY(rocprim::radix_sort_pairs(nullptr, need, key_in, key_out, static_cast<const V*>(val_in),
-                                            static_cast<V*>(val_out), (size_t)nnz, 0, key_bits, s));
-    if (need > temp_bytes) return INSUM_ERR_CAPACITY;
-    INSUM_HIP_TRY(rocprim::radix_sort_pairs(temp, need, key_in, key_out, static_cast<const V*>(val_in),
-                                            static_cast<V*>(val_out), (size_t)nnz, 0, key_bits, s));
-    return INSUM_OK;
+size_t convert_temp_bytes(int64_t nnz, int64_t longest_scan) {
+    return std::max(sort_temp_bytes(nnz), scan_temp_bytes(longest_scan));
 }
 
 insum_status read_flags(const Flags* d_flags, Flags* h, hipStream_t s) {
     INSUM_HIP_TRY(hipMemcpyAsync(h, d_flags, sizeof(Flags), hipMemcpyDeviceToHost, s));
     INSUM_HIP_TRY(hipStreamSynchronize(s));
     return INSUM_OK;
+}
+
+// ---- typed bodies of the entry points (KeyT = uint32_t when every key fits, else uint64_t) ----
+struct Buffers {  // carved from the caller's workspace
+    Flags* flags;
+    int32_t *cnt, *start, *grp_start;  // per row (block row, offset): counts / first entry / first group
+    void* key[2];
+    void* val[2];
+    int32_t *head, *blk_ord;  // block format only
+    void* temp;
+    size_t temp_bytes;
+};
+
+template <typename KeyT, typename V>
+insum_status group_sort_and_bounds(const Buffers& b, int64_t M, int64_t K, int64_t nnz, const int32_t* row,
+                                   const int32_t* col, const void* val, int32_t g, hipStream_t s,
+                                   const KeyT** sorted_key, const V** sorted_val) {
+    KeyT* const keys[2] = {static_cast<KeyT*>(b.key[0]), static_cast<KeyT*>(b.key[1])};
+    V* const vals[2] = {static_cast<V*>(b.val[0]), static_cast<V*>(b.val[1])};
+    hipLaunchKernelGGL((k_group_keys<KeyT, false>), dim3(blocks_for(nnz)), dim3(kThreads), 0, s, M, K, nnz, row,
+                       col, keys[0], b.cnt, b.flags);
+    INSUM_HIP_TRY(hipGetLastError());
+    const int where = radix_sort_pairs<KeyT, V>(b.temp, b.temp_bytes, keys, static_cast<const V*>(val), vals, nnz,
+                                                bits_for((uint64_t)M * (uint64_t)K - 1), s);
+    if (where < 0) return (insum_status)(-where);
+    *sorted_key = keys[where];
+    *sorted_val = vals[where];
+    hipLaunchKernelGGL(k_row_bounds<KeyT>, dim3(blocks_for(nnz + 1)), dim3(kThreads), 0, s, nnz, M,
+                       Divisor((uint64_t)K), *sorted_key, b.start);
+    hipLaunchKernelGGL(k_groups_from_bounds, dim3(blocks_for(M + 1)), dim3(kThreads), 0, s, M, b.start, g, b.cnt);
+    INSUM_HIP_TRY(hipGetLastError());
+    return INSUM_OK;
+}
+
+// Everything of insum_coo_to_groupcoo after argument checking.
+template <typename KeyT, typename V>
+insum_status group_convert(const Buffers& b, int64_t M, int64_t K, int64_t nnz, const int32_t* row,
+                           const int32_t* col, const void* val, int32_t g, bool fill, int64_t* num_groups,
+                           int32_t* AM, int32_t* AK, void* AV, int64_t capacity_groups, hipStream_t s) {
+    insum_status st;
+    const KeyT* skey = nullptr;
+    const V* sval = nullptr;
+    hipLaunchKernelGGL(k_zero_i32, dim3(1), dim3(kThreads), 0, s, reinterpret_cast<int32_t*>(b.flags),
+                       (int64_t)(sizeof(Flags) / 4));
+    if (!fill) {  // count mode: atomic histogram of the rows, no sort
+        hipLaunchKernelGGL(k_zero_i32, dim3(blocks_for(M + 1)), dim3(kThreads), 0, s, b.cnt, M + 1);
+        hipLaunchKernelGGL((k_group_keys<KeyT, true>), dim3(blocks_for(nnz)), dim3(kThreads), 0, s, M, K, nnz, row,
+                           col, static_cast<KeyT*>(nullptr), b.cnt, b.flags);
+        hipLaunchKernelGGL(k_groups_from_counts, dim3(blocks_for(M + 1)), dim3(kThreads), 0, s, M, b.cnt, g);
+    } else {
+        st = group_sort_and_bounds<KeyT, V>(b, M, K, nnz, row, col, val, g, s, &skey, &sval);
+        if (st != INSUM_OK) return st;
+    }
+    st = scan_exclusive(b.temp, b.temp_bytes, b.cnt, b.grp_start, M + 1, s);
+    if (st != INSUM_OK) return st;
+    hipLaunchKernelGGL(k_store_total, dim3(1), dim3(1), 0, s, b.grp_start + M, &b.flags->total_a);
+    INSUM_HIP_TRY(hipGetLastError());
+    Flags h;
+    st = read_flags(b.flags, &h, s);
+    if (st != INSUM_OK) return st;
+    if (h.out_of_range) return INSUM_ERR_OUT_OF_RANGE;
+    const int64_t G = h.total_a;
+    *num_groups = G;
+    if (!fill) return INSUM_OK;
+    if (capacity_groups < G) return INSUM_ERR_CAPACITY;
+    hipLaunchKernelGGL((k_group_fill<KeyT, V>), dim3(blocks_for(nnz)), dim3(kThreads), 0, s, Divisor((uint64_t)K),
+                       nnz, g, skey, sval, b.start, b.grp_start, AM, AK, static_cast<V*>(AV));
+    INSUM_HIP_TRY(hipGetLastError());
+    INSUM_HIP_TRY(hipStreamSynchronize(s));
+    return INSUM_OK;
+}
+
+// What a count call of the block conversion leaves at the front of the workspace, so that a
+// fill call with the same arguments can go on from the sorted entries instead of sorting again.
+struct BlockState {
+    uint64_t magic;
+    int64_t M, K, nnz, num_blocks;
+    const void *row, *col, *val;
+    int32_t bM, bK, dt, which;  // which: buffer pair that holds the sorted entries
+};
+constexpr uint64_t kBlockStateMagic = 0x31544154534b4c42ull;
+
+__global__ void k_store_block_state(BlockState* dst, BlockState v) { *dst = v; }
+
+template <typename KeyT, typename V>
+insum_status block_convert(const Buffers& b, BlockState* d_state, bool resume, int resume_which,
+                           int64_t resume_blocks, int64_t M, int64_t K, int64_t nnz, const int32_t* row,
+                           const int32_t* col, const void* val, insum_dtype dt, int32_t bM, int32_t bK, int32_t g,
+                           bool fill, int32_t* g_used, int64_t* num_groups, int32_t* AM, int32_t* AK, void* AV,
+                           int64_t capacity_groups, hipStream_t s) {
+    const int64_t nbr = M / bM;
+    const Divisor per_block((uint64_t)bM * (uint64_t)bK);
+    const Divisor blocks_per_row((uint64_t)(K / bK));
+    KeyT* const keys[2] = {static_cast<KeyT*>(b.key[0]), static_cast<KeyT*>(b.key[1])};
+    V* const vals[2] = {static_cast<V*>(b.val[0]), static_cast<V*>(b.val[1])};
+    insum_status st;
+    Flags h;
+    int where = resume_which;
+    int64_t num_blocks = resume_blocks;
+    if (!resume) {
+        hipLaunchKernelGGL(k_zero_i32, dim3(blocks_for(nbr + 1)), dim3(kThreads), 0, s, b.cnt, nbr + 1);
+        hipLaunchKernelGGL(k_zero_i32, dim3(1), dim3(kThreads), 0, s, reinterpret_cast<int32_t*>(b.flags),
+                           (int64_t)(sizeof(Flags) / 4));
+        hipLaunchKernelGGL(k_block_keys<KeyT>, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, M, K, nnz, bM, bK, row,
+                           col, keys[0], b.flags);
+        INSUM_HIP_TRY(hipGetLastError());
+        where = radix_sort_pairs<KeyT, V>(b.temp, b.temp_bytes, keys, static_cast<const V*>(val), vals, nnz,
+                                          bits_for((uint64_t)M * (uint64_t)K - 1), s);
+        if (where < 0) return (insum_status)(-where);
+        hipLaunchKernelGGL(k_block_heads<KeyT>, dim3(blocks_for(nnz + 1)), dim3(kThreads), 0, s, nnz, per_block,
+                           blocks_per_row, (const KeyT*)keys[where], b.head, b.cnt, b.flags);
+        st = scan_exclusive(b.temp, b.temp_bytes, b.head, b.blk_ord, nnz + 1, s);
+        if (st != INSUM_OK) return st;
+        st = scan_exclusive(b.temp, b.temp_bytes, b.cnt, b.start, nbr + 1, s);
+        if (st != INSUM_OK) return st;
+        hipLaunchKernelGGL(k_store_total, dim3(1), dim3(1), 0, s, b.start + nbr, &b.flags->total_a);
+        INSUM_HIP_TRY(hipGetLastError());
+        st = read_flags(b.flags, &h, s);
+        if (st != INSUM_OK) return st;
+        if (h.out_of_range) return INSUM_ERR_OUT_OF_RANGE;
+        if (h.duplicate) return INSUM_ERR_DUPLICATE;
+        num_blocks = h.total_a;
+    }
+    if (g == 0) g = insum_default_group_size(num_blocks, nbr);
+    *g_used = g;
+
+    // groups per block row from the block counts (start[] holds their prefix sums)
+    hipLaunchKernelGGL(k_groups_from_bounds, dim3(blocks_for(nbr + 1)), dim3(kThreads), 0, s, nbr, b.start, g, b.cnt);
+    st = scan_exclusive(b.temp, b.temp_bytes, b.cnt, b.grp_start, nbr + 1, s);
+    if (st != INSUM_OK) return st;
+    hipLaunchKernelGGL(k_store_total, dim3(1), dim3(1), 0, s, b.grp_start + nbr, &b.flags->total_b);
+    if (!fill) {
+        BlockState v{};
+        v.magic = kBlockStateMagic;
+        v.M = M; v.K = K; v.nnz = nnz; v.num_blocks = num_blocks;
+        v.row = row; v.col = col; v.val = val;
+        v.bM = bM; v.bK = bK; v.dt = (int32_t)dt; v.which = where;
+        hipLaunchKernelGGL(k_store_block_state, dim3(1), dim3(1), 0, s, d_state, v);
+    }
+    INSUM_HIP_TRY(hipGetLastError());
+    st = read_flags(b.flags, &h, s);
+    if (st != INSUM_OK) return st;
+    const int64_t G = h.total_b;
+    *num_groups = G;
+    if (!fill) return INSUM_OK;
+    if (capacity_groups < G) return INSUM_ERR_CAPACITY;
+
+    const int64_t av_elems = G * g * (int64_t)bM * bK;
+    hipLaunchKernelGGL(k_fill_zero<V>, dim3(blocks_for(av_elems)), dim3(kThreads), 0, s, static_cast<V*>(AV), av_elems);
+    hipLaunchKernelGGL((k_block_fill<KeyT, V>), dim3(blocks_for(nnz)), dim3(kThreads), 0, s, per_block,
+                       blocks_per_row, nnz, g, (const KeyT*)keys[where], (const V*)vals[where], b.head, b.blk_ord,
+                       b.start, b.grp_start, AM, AK, static_cast<V*>(AV));
+    // the entries have been consumed: a later fill call must sort again
+    hipLaunchKernelGGL(k_zero_i32, dim3(1), dim3(kThreads), 0, s, reinterpret_cast<int32_t*>(d_state), (int64_t)2);
+    INSUM_HIP_TRY(hipGetLastError());
+    INSUM_HIP_TRY(hipStreamSynchronize(s));
+    return INSUM_OK;
+}
+
+template <typename KeyT, typename V>
+insum_status map_convert(const Buffers& b, int64_t X, int64_t Y, int64_t Z, int64_t nnz, const int32_t* mx,
+                         const int32_t* my, const int32_t* mz, const void* mv, int32_t g, bool fill,
+                         int64_t* num_groups, int32_t* MAPZ, int32_t* MAPX, int32_t* MAPY, void* MAPV,
+                         int64_t capacity_groups, hipStream_t s) {
+    const Divisor per_z((uint64_t)X);
+    const dim3 grid_nnz(blocks_for(nnz)), block(kThreads);
+    KeyT* const keys[2] = {static_cast<KeyT*>(b.key[0]), static_cast<KeyT*>(b.key[1])};
+    uint64_t* const pays[2] = {static_cast<uint64_t*>(b.val[0]), static_cast<uint64_t*>(b.val[1])};
+    const KeyT* skey = nullptr;
+    const uint64_t* spay = nullptr;
+    insum_status st;
+    hipLaunchKernelGGL(k_zero_i32, dim3(1), block, 0, s, reinterpret_cast<int32_t*>(b.flags),
+                       (int64_t)(sizeof(Flags) / 4));
+    if (!fill) {
+        hipLaunchKernelGGL(k_zero_i32, dim3(blocks_for(Z + 1)), block, 0, s, b.cnt, Z + 1);
+        hipLaunchKernelGGL((k_map_keys<KeyT, V, true>), grid_nnz, block, 0, s, X, Y, Z, nnz, mx, my, mz,
+                           static_cast<const V*>(nullptr), static_cast<KeyT*>(nullptr),
+                           static_cast<uint64_t*>(nullptr), b.cnt, b.flags);
+        hipLaunchKernelGGL(k_groups_from_counts, dim3(blocks_for(Z + 1)), block, 0, s, Z, b.cnt, g);
+    } else {
+        hipLaunchKernelGGL((k_map_keys<KeyT, V, false>), grid_nnz, block, 0, s, X, Y, Z, nnz, mx, my, mz,
+                           static_cast<const V*>(mv), keys[0], pays[0], b.cnt, b.flags);
+        INSUM_HIP_TRY(hipGetLastError());
+        const int where = radix_sort_pairs<KeyT, uint64_t>(b.temp, b.temp_bytes, keys, (const uint64_t*)pays[0], pays,
+                                                           nnz, bits_for((uint64_t)Z * (uint64_t)X - 1), s);
+        if (where < 0) return (insum_status)(-where);
+        skey = keys[where];
+        spay = pays[where];
+        hipLaunchKernelGGL(k_row_bounds<KeyT>, dim3(blocks_for(nnz + 1)), block, 0, s, nnz, Z, per_z, skey, b.start);
+        hipLaunchKernelGGL(k_groups_from_bounds, dim3(blocks_for(Z + 1)), block, 0, s, Z, b.start, g, b.cnt);
+    }
+    st = scan_exclusive(b.temp, b.temp_bytes, b.cnt, b.grp_start, Z + 1, s);
+    if (st != INSUM_OK) return st;
+    hipLaunchKernelGGL(k_store_total, dim3(1), dim3(1), 0, s, b.grp_start + Z, &b.flags->total_a);
+    INSUM_HIP_TRY(hipGetLastError());
+    Flags h;
+    st = read_flags(b.flags, &h, s);
+    if (st != INSUM_OK) return st;
+    if (h.out_of_range) return INSUM_ERR_OUT_OF_RANGE;
+    const int64_t G = h.total_a;
+    *num_groups = G;
+    if (!fill) return INSUM_OK;
+    if (capacity_groups < G) return INSUM_ERR_CAPACITY;
+    hipLaunchKernelGGL((k_map_fill<KeyT, V>), grid_nnz, block, 0, s, per_z, nnz, g, skey, spay, b.start, b.grp_start,
+                       MAPZ, MAPX, MAPY, static_cast<V*>(MAPV));
+    INSUM_HIP_TRY(hipGetLastError());
+    INSUM_HIP_TRY(hipStreamSynchronize(s));
+    return INSUM_OK;
+}
+
+// Workspace layout shared by the three conversions: rows = number of rows / block rows / offsets,
+// val_bytes = size of one sorted payload, with_heads = the block format's two extra arrays.
+size_t conversion_workspace_bytes(int64_t rows, int64_t nnz, size_t val_bytes, bool with_heads) {
+    const size_t n1 = (size_t)std::max<int64_t>(nnz, 1);
+    size_t b = 512;
+    b += align_up(sizeof(BlockState), 256) + align_up(sizeof(Flags), 256);
+    b += 3 * align_up((size_t)(rows + 1) * 4, 256);
+    b += 2 * align_up(n1 * 8, 256);          // keys, two buffers
+    b += 2 * align_up(n1 * val_bytes, 256);  // payloads, two buffers
+    if (with_heads) b += 2 * align_up((size_t)(nnz + 1) * 4, 256);
+    b += align_up(convert_temp_bytes(nnz, std::max(rows + 1, with_heads ? nnz + 1 : 0)), 256);
+    return b;
+}
+
+bool carve(Carver& ws, Buffers& b, BlockState** state, int64_t rows, int64_t nnz, size_t val_bytes,
+           bool with_heads) {
+    *state = ws.take<BlockState>(1);
+    b.flags = ws.take<Flags>(1);
+    b.cnt = ws.take<int32_t>(rows + 1);
+    b.start = ws.take<int32_t>(rows + 1);
+    b.grp_start = ws.take<int32_t>(rows + 1);
+    b.key[0] = ws.take<uint64_t>(nnz);
+    b.key[1] = ws.take<uint64_t>(nnz);
+    b.val[0] = ws.take<char>((size_t)std::max<int64_t>(nnz, 1) * val_bytes);
+    b.val[1] = ws.take<char>((size_t)std::max<int64_t>(nnz, 1) * val_bytes);
+    b.head = with_heads ? ws.take<int32_t>(nnz + 1) : nullptr;
+    b.blk_ord = with_heads ? ws.take<int32_t>(nnz + 1) : nullptr;
+    b.temp_bytes = convert_temp_bytes(nnz, std::max(rows + 1, with_heads ? nnz + 1 : 0));
+    b.temp = ws.take<char>(b.temp_bytes);
+    return ws.ok;
 }
 
 }  // namespace
@@ -363,16 +575,7 @@ using namespace insum;
 
 // ============================================================================================
 extern "C" size_t insum_coo_to_groupcoo_workspace_bytes(int64_t M, int64_t nnz) {
-    M = std::max<int64_t>(M, 0);
-    nnz = std::max<int64_t>(nnz, 0);
-    const size_t n1 = (size_t)std::max<int64_t>(nnz, 1);
-    size_t b = 512;
-    b += align_up(sizeof(Flags), 256);
-    b += 3 * align_up((size_t)(M + 1) * 4, 256);  // groups per row, row_start, grp_start
-    b += 2 * align_up(n1 * 8, 256);               // keys in/out
-    b += align_up(n1 * 4, 256);                   // sorted values
-    b += align_up(std::max(sort_temp_bytes(nnz), scan_temp_bytes(M + 1)), 256);
-    return b;
+    return conversion_workspace_bytes(std::max<int64_t>(M, 0), std::max<int64_t>(nnz, 0), 4, false);
 }
 
 extern "C" insum_status insum_coo_to_groupcoo(int64_t M, int64_t K, int64_t nnz, const int32_t* row,
@@ -395,64 +598,18 @@ extern "C" insum_status insum_coo_to_groupcoo(int64_t M, int64_t K, int64_t nnz,
     hipStream_t s = static_cast<hipStream_t>(stream);
 
     Carver ws(workspace, workspace_bytes);
-    Flags* d_flags = ws.take<Flags>(1);
-    int32_t* gpr = ws.take<int32_t>(M + 1);  // per-row counts, then groups per row
-    int32_t* row_start = ws.take<int32_t>(M + 1);
-    int32_t* grp_start = ws.take<int32_t>(M + 1);
-    uint64_t* key_a = ws.take<uint64_t>(nnz);
-    uint64_t* key_b = ws.take<uint64_t>(nnz);
-    uint32_t* val_b = ws.take<uint32_t>(nnz);
-    const size_t temp_bytes = std::max(sort_temp_bytes(nnz), scan_temp_bytes(M + 1));
-    void* temp = ws.take<char>(temp_bytes);
-    if (!ws.ok) return INSUM_ERR_CAPACITY;
-
-    const Divisor per_row((uint64_t)K);
-    insum_status st;
-    hipLaunchKernelGGL(k_zero_i32, dim3(1), dim3(kThreads), 0, s, reinterpret_cast<int32_t*>(d_flags),
-                       (int64_t)(sizeof(Flags) / 4));
-    if (!fill) {  // count mode: atomic histogram of the rows, no sort
-        hipLaunchKernelGGL(k_zero_i32, dim3(blocks_for(M + 1)), dim3(kThreads), 0, s, gpr, M + 1);
-        hipLaunchKernelGGL(k_group_keys<true>, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, M, K, nnz, row,
-                           col, key_a, gpr, d_flags);
-        hipLaunchKernelGGL(k_groups_from_counts, dim3(blocks_for(M + 1)), dim3(kThreads), 0, s, M, gpr, g);
-    } else {
-        hipLaunchKernelGGL(k_group_keys<false>, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, M, K, nnz, row,
-                           col, key_a, gpr, d_flags);
-        INSUM_HIP_TRY(hipGetLastError());
-        const int key_bits = bits_for((uint64_t)M * (uint64_t)K - 1);
-        st = dtype_size(dt) == 4
-                 ? sort_by_key<uint32_t>(temp, temp_bytes, key_a, key_b, val, val_b, nnz, key_bits, s)
-                 : sort_by_key<uint16_t>(temp, temp_bytes, key_a, key_b, val, val_b, nnz, key_bits, s);
-        if (st != INSUM_OK) return st;
-        hipLaunchKernelGGL(k_row_bounds, dim3(blocks_for(nnz + 1)), dim3(kThreads), 0, s, nnz, M, per_row,
-                           key_b, row_start);
-        hipLaunchKernelGGL(k_groups_from_bounds, dim3(blocks_for(M + 1)), dim3(kThreads), 0, s, M, row_start,
-                           g, gpr);
-    }
-    st = scan_exclusive(temp, temp_bytes, gpr, grp_start, M + 1, s);
-    if (st != INSUM_OK) return st;
-    hipLaunchKernelGGL(k_store_total, dim3(1), dim3(1), 0, s, grp_start + M, &d_flags->total_a);
-    INSUM_HIP_TRY(hipGetLastError());
-    Flags h;
-    st = read_flags(d_flags, &h, s);
-    if (st != INSUM_OK) return st;
-    if (h.out_of_range) return INSUM_ERR_OUT_OF_RANGE;
-    const int64_t G = h.total_a;
-    *num_groups = G;
-    if (!fill) return INSUM_OK;
-    if (capacity_groups < G) return INSUM_ERR_CAPACITY;
-
-    if (dtype_size(dt) == 4)
-        hipLaunchKernelGGL(k_group_fill<uint32_t>, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, per_row, nnz, g,
-                           key_b, reinterpret_cast<const uint32_t*>(val_b), row_start, grp_start, AM, AK,
-                           static_cast<uint32_t*>(AV));
-    else
-        hipLaunchKernelGGL(k_group_fill<uint16_t>, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, per_row, nnz, g,
-                           key_b, reinterpret_cast<const uint16_t*>(val_b), row_start, grp_start, AM, AK,
-                           static_cast<uint16_t*>(AV));
-    INSUM_HIP_TRY(hipGetLastError());
-    INSUM_HIP_TRY(hipStreamSynchronize(s));
-    return INSUM_OK;
+    Buffers b;
+    BlockState* unused = nullptr;
+    if (!carve(ws, b, &unused, M, nnz, 4, false)) return INSUM_ERR_CAPACITY;
+    const bool narrow = bits_for((uint64_t)M * (uint64_t)K - 1) <= 32;
+    const bool wide_val = dtype_size(dt) == 4;
+#define INSUM_GROUP_CASE(KeyT, V) \
+    return group_convert<KeyT, V>(b, M, K, nnz, row, col, val, g, fill, num_groups, AM, AK, AV, capacity_groups, s)
+    if (narrow && wide_val) INSUM_GROUP_CASE(uint32_t, uint32_t);
+    if (narrow) INSUM_GROUP_CASE(uint32_t, uint16_t);
+    if (wide_val) INSUM_GROUP_CASE(uint64_t, uint32_t);
+    INSUM_GROUP_CASE(uint64_t, uint16_t);
+#undef INSUM_GROUP_CASE
 }
 
 // ============================================================================================
@@ -461,17 +618,7 @@ extern "C" size_t insum_coo_to_blockgroupcoo_workspace_bytes(int64_t M, int64_t 
     (void)K;
     (void)bK;
     M = std::max<int64_t>(M, 0);
-    nnz = std::max<int64_t>(nnz, 0);
-    const int64_t nbr = bM > 0 ? M / bM : M;
-    const size_t n1 = (size_t)std::max<int64_t>(nnz, 1);
-    size_t b = 512;
-    b += align_up(sizeof(Flags), 256);
-    b += 3 * align_up((size_t)(nbr + 1) * 4, 256);  // occ, brow_start, grp_start
-    b += 2 * align_up(n1 * 8, 256);                 // keys in/out
-    b += align_up(n1 * 4, 256);                     // sorted values
-    b += 2 * align_up((size_t)(nnz + 1) * 4, 256);  // head flags, block ordinals
-    b += align_up(std::max({sort_temp_bytes(nnz), scan_temp_bytes(nnz + 1), scan_temp_bytes(nbr + 1)}), 256);
-    return b;
+    return conversion_workspace_bytes(bM > 0 ? M / bM : M, std::max<int64_t>(nnz, 0), 4, true);
 }
 
 extern "C" insum_status insum_coo_to_blockgroupcoo(int64_t M, int64_t K, int64_t nnz,
@@ -489,7 +636,6 @@ extern "C" insum_status insum_coo_to_blockgroupcoo(int64_t M, int64_t K, int64_t
     if (nnz > 0 && (!row || !col || !val)) return INSUM_ERR_INVALID_ARG;
     const bool fill = AM || AK || AV;
     if (fill && (!AM || !AK || !AV || capacity_groups < 0)) return INSUM_ERR_INVALID_ARG;
-    const int64_t nbr = M / bM;
     *g_used = g ? g : 1;
     *num_groups = 0;
     if (nnz == 0) return INSUM_OK;
@@ -497,93 +643,36 @@ extern "C" insum_status insum_coo_to_blockgroupcoo(int64_t M, int64_t K, int64_t
     hipStream_t s = static_cast<hipStream_t>(stream);
 
     Carver ws(workspace, workspace_bytes);
-    Flags* d_flags = ws.take<Flags>(1);
-    int32_t* occ = ws.take<int32_t>(nbr + 1);
-    int32_t* brow_start = ws.take<int32_t>(nbr + 1);
-    int32_t* grp_start = ws.take<int32_t>(nbr + 1);
-    uint64_t* key_a = ws.take<uint64_t>(nnz);
-    uint64_t* key_b = ws.take<uint64_t>(nnz);
-    uint32_t* val_b = ws.take<uint32_t>(nnz);
-    int32_t* head = ws.take<int32_t>(nnz + 1);
-    int32_t* blk_ord = ws.take<int32_t>(nnz + 1);
-    const size_t temp_bytes =
-        std::max({sort_temp_bytes(nnz), scan_temp_bytes(nnz + 1), scan_temp_bytes(nbr + 1)});
-    void* temp = ws.take<char>(temp_bytes);
-    if (!ws.ok) return INSUM_ERR_CAPACITY;
+    Buffers b;
+    BlockState* d_state = nullptr;
+    if (!carve(ws, b, &d_state, M / bM, nnz, 4, true)) return INSUM_ERR_CAPACITY;
 
-    const Divisor per_block((uint64_t)bM * (uint64_t)bK);
-    const Divisor blocks_per_row((uint64_t)(K / bK));
-    hipLaunchKernelGGL(k_zero_i32, dim3(blocks_for(nbr + 1)), dim3(kThreads), 0, s, occ, nbr + 1);
-    hipLaunchKernelGGL(k_zero_i32, dim3(1), dim3(kThreads), 0, s, reinterpret_cast<int32_t*>(d_flags),
-                       (int64_t)(sizeof(Flags) / 4));
-    hipLaunchKernelGGL(k_block_keys, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, M, K, nnz, bM, bK, row,
-                       col, key_a, d_flags);
-    INSUM_HIP_TRY(hipGetLastError());
-    const int key_bits = bits_for((uint64_t)M * (uint64_t)K - 1);
-    insum_status st =
-        dtype_size(dt) == 4
-            ? sort_by_key<uint32_t>(temp, temp_bytes, key_a, key_b, val, val_b, nnz, key_bits, s)
-            : sort_by_key<uint16_t>(temp, temp_bytes, key_a, key_b, val, val_b, nnz, key_bits, s);
-    if (st != INSUM_OK) return st;
-    hipLaunchKernelGGL(k_block_heads, dim3(blocks_for(nnz + 1)), dim3(kThreads), 0, s, nnz, per_block,
-                       blocks_per_row, key_b, head, occ, d_flags);
-    st = scan_exclusive(temp, temp_bytes, head, blk_ord, nnz + 1, s);
-    if (st != INSUM_OK) return st;
-    st = scan_exclusive(temp, temp_bytes, occ, brow_start, nbr + 1, s);
-    if (st != INSUM_OK) return st;
-    hipLaunchKernelGGL(k_store_total, dim3(1), dim3(1), 0, s, brow_start + nbr, &d_flags->total_a);
-    INSUM_HIP_TRY(hipGetLastError());
-    Flags h;
-    st = read_flags(d_flags, &h, s);
-    if (st != INSUM_OK) return st;
-    if (h.out_of_range) return INSUM_ERR_OUT_OF_RANGE;
-    if (h.duplicate) return INSUM_ERR_DUPLICATE;
-    const int64_t num_blocks = h.total_a;
-    if (g == 0) g = insum_default_group_size(num_blocks, nbr);
-    *g_used = g;
-
-    hipLaunchKernelGGL(k_groups_from_counts, dim3(blocks_for(nbr + 1)), dim3(kThreads), 0, s, nbr, occ, g);
-    st = scan_exclusive(temp, temp_bytes, occ, grp_start, nbr + 1, s);
-    if (st != INSUM_OK) return st;
-    hipLaunchKernelGGL(k_store_total, dim3(1), dim3(1), 0, s, grp_start + nbr, &d_flags->total_b);
-    INSUM_HIP_TRY(hipGetLastError());
-    st = read_flags(d_flags, &h, s);
-    if (st != INSUM_OK) return st;
-    const int64_t G = h.total_b;
-    *num_groups = G;
-    if (!fill) return INSUM_OK;
-    if (capacity_groups < G) return INSUM_ERR_CAPACITY;
-
-    const int64_t av_elems = G * g * (int64_t)bM * bK;
-    if (dtype_size(dt) == 4) {
-        hipLaunchKernelGGL(k_fill_zero<uint32_t>, dim3(blocks_for(av_elems)), dim3(kThreads), 0, s,
-                           static_cast<uint32_t*>(AV), av_elems);
-        hipLaunchKernelGGL(k_block_fill<uint32_t>, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, per_block,
-                           blocks_per_row, nnz, g, key_b, reinterpret_cast<const uint32_t*>(val_b), head,
-                           blk_ord, brow_start, grp_start, AM, AK, static_cast<uint32_t*>(AV));
-    } else {
-        hipLaunchKernelGGL(k_fill_zero<uint16_t>, dim3(blocks_for(av_elems)), dim3(kThreads), 0, s,
-                           static_cast<uint16_t*>(AV), av_elems);
-        hipLaunchKernelGGL(k_block_fill<uint16_t>, dim3(blocks_for(nnz)), dim3(kThreads), 0, s, per_block,
-                           blocks_per_row, nnz, g, key_b, reinterpret_cast<const uint16_t*>(val_b), head,
-                           blk_ord, brow_start, grp_start, AM, AK, static_cast<uint16_t*>(AV));
+    // A fill call right after a count call with the same arguments finds that call's sorted
+    // entries, block ordinals and block-row bounds still in the workspace.
+    bool resume = false;
+    BlockState st{};
+    if (fill) {
+        INSUM_HIP_TRY(hipMemcpyAsync(&st, d_state, sizeof(st), hipMemcpyDeviceToHost, s));
+        INSUM_HIP_TRY(hipStreamSynchronize(s));
+        resume = st.magic == kBlockStateMagic && st.M == M && st.K == K && st.nnz == nnz && st.row == row &&
+                 st.col == col && st.val == val && st.bM == bM && st.bK == bK && st.dt == (int32_t)dt &&
+                 (st.which == 0 || st.which == 1);
     }
-    INSUM_HIP_TRY(hipGetLastError());
-    INSUM_HIP_TRY(hipStreamSynchronize(s));
-    return INSUM_OK;
+    const bool narrow = bits_for((uint64_t)M * (uint64_t)K - 1) <= 32;
+    const bool wide_val = dtype_size(dt) == 4;
+#define INSUM_BLOCK_CASE(KeyT, V)                                                                              \
+    return block_convert<KeyT, V>(b, d_state, resume, st.which, st.num_blocks, M, K, nnz, row, col, val, dt, bM, bK, \
+                                  g, fill, g_used, num_groups, AM, AK, AV, capacity_groups, s)
+    if (narrow && wide_val) INSUM_BLOCK_CASE(uint32_t, uint32_t);
+    if (narrow) INSUM_BLOCK_CASE(uint32_t, uint16_t);
+    if (wide_val) INSUM_BLOCK_CASE(uint64_t, uint32_t);
+    INSUM_BLOCK_CASE(uint64_t, uint16_t);
+#undef INSUM_BLOCK_CASE
 }
 
 // ============================================================================================
 extern "C" size_t insum_map_to_groupcoo_workspace_bytes(int64_t Z, int64_t nnz) {
-    Z = std::max<int64_t>(Z, 0);
-    nnz = std::max<int64_t>(nnz, 0);
-    const size_t n1 = (size_t)std::max<int64_t>(nnz, 1);
-    size_t b = 512;
-    b += align_up(sizeof(Flags), 256);
-    b += 3 * align_up((size_t)(Z + 1) * 4, 256);  // groups per offset, z_start, grp_start
-    b += 4 * align_up(n1 * 8, 256);               // keys in/out, payloads in/out
-    b += align_up(std::max(sort_temp_bytes_map(nnz), scan_temp_bytes(Z + 1)), 256);
-    return b;
+    return conversion_workspace_bytes(std::max<int64_t>(Z, 0), std::max<int64_t>(nnz, 0), 8, false);
 }
 
 extern "C" insum_status insum_map_to_groupcoo(int64_t X, int64_t Y, int64_t Z, int64_t nnz,
@@ -607,63 +696,17 @@ extern "C" insum_status insum_map_to_groupcoo(int64_t X, int64_t Y, int64_t Z, i
     hipStream_t s = static_cast<hipStream_t>(stream);
 
     Carver ws(workspace, workspace_bytes);
-    Flags* d_flags = ws.take<Flags>(1);
-    int32_t* gpz = ws.take<int32_t>(Z + 1);  // per-offset counts, then groups per offset
-    int32_t* z_start = ws.take<int32_t>(Z + 1);
-    int32_t* grp_start = ws.take<int32_t>(Z + 1);
-    uint64_t* key_a = ws.take<uint64_t>(nnz);
-    uint64_t* key_b = ws.take<uint64_t>(nnz);
-    uint64_t* pay_a = ws.take<uint64_t>(nnz);
-    uint64_t* pay_b = ws.take<uint64_t>(nnz);
-    const size_t temp_bytes = std::max(sort_temp_bytes_map(nnz), scan_temp_bytes(Z + 1));
-    void* temp = ws.take<char>(temp_bytes);
-    if (!ws.ok) return INSUM_ERR_CAPACITY;
-
-    const Divisor per_z((uint64_t)X);
-    const bool wide = dtype_size(dt) == 4;
-    const dim3 grid_nnz(blocks_for(nnz)), block(kThreads);
-    insum_status st;
-    hipLaunchKernelGGL(k_zero_i32, dim3(1), block, 0, s, reinterpret_cast<int32_t*>(d_flags),
-                       (int64_t)(sizeof(Flags) / 4));
-    if (!fill) {
-        hipLaunchKernelGGL(k_zero_i32, dim3(blocks_for(Z + 1)), block, 0, s, gpz, Z + 1);
-        hipLaunchKernelGGL((k_map_keys<uint16_t, true>), grid_nnz, block, 0, s, X, Y, Z, nnz, mx, my, mz,
-                           static_cast<const uint16_t*>(nullptr), key_a, pay_a, gpz, d_flags);
-        hipLaunchKernelGGL(k_groups_from_counts, dim3(blocks_for(Z + 1)), block, 0, s, Z, gpz, g);
-    } else {
-        if (wide)
-            hipLaunchKernelGGL((k_map_keys<uint32_t, false>), grid_nnz, block, 0, s, X, Y, Z, nnz, mx, my, mz,
-                               static_cast<const uint32_t*>(mv), key_a, pay_a, gpz, d_flags);
-        else
-            hipLaunchKernelGGL((k_map_keys<uint16_t, false>), grid_nnz, block, 0, s, X, Y, Z, nnz, mx, my, mz,
-                               static_cast<const uint16_t*>(mv), key_a, pay_a, gpz, d_flags);
-        INSUM_HIP_TRY(hipGetLastError());
-        const int key_bits = bits_for((uint64_t)Z * (uint64_t)X - 1);
-        st = sort_by_key<uint64_t>(temp, temp_bytes, key_a, key_b, pay_a, pay_b, nnz, key_bits, s);
-        if (st != INSUM_OK) return st;
-        hipLaunchKernelGGL(k_row_bounds, dim3(blocks_for(nnz + 1)), block, 0, s, nnz, Z, per_z, key_b, z_start);
-        hipLaunchKernelGGL(k_groups_from_bounds, dim3(blocks_for(Z + 1)), block, 0, s, Z, z_start, g, gpz);
-    }
-    st = scan_exclusive(temp, temp_bytes, gpz, grp_start, Z + 1, s);
-    if (st != INSUM_OK) return st;
-    hipLaunchKernelGGL(k_store_total, dim3(1), dim3(1), 0, s, grp_start + Z, &d_flags->total_a);
-    INSUM_HIP_TRY(hipGetLastError());
-    Flags h;
-    st = read_flags(d_flags, &h, s);
-    if (st != INSUM_OK) return st;
-    if (h.out_of_range) return INSUM_ERR_OUT_OF_RANGE;
-    const int64_t G = h.total_a;
-    *num_groups = G;
-    if (!fill) return INSUM_OK;
-    if (capacity_groups < G) return INSUM_ERR_CAPACITY;
-
-    if (wide)
-        hipLaunchKernelGGL(k_map_fill<uint32_t>, grid_nnz, block, 0, s, per_z, nnz, g, key_b, pay_b, z_start,
-                           grp_start, MAPZ, MAPX, MAPY, static_cast<uint32_t*>(MAPV));
-    else
-        hipLaunchKernelGGL(k_map_fill<uint16_t>, grid_nnz, block, 0, s, per_z, nnz, g, key_b, pay_b, z_start,
-                           grp_start, MAPZ, MAPX, MAPY, static_cast<uint16_t*>(MAPV));
-    INSUM_HIP_TRY(hipGetLastError());
-    INSUM_HIP_TRY(hipStreamSynchronize(s));
-    return INSUM_OK;
+    Buffers b;
+    BlockState* unused = nullptr;
+    if (!carve(ws, b, &unused, Z, nnz, 8, false)) return INSUM_ERR_CAPACITY;
+    const bool narrow = bits_for((uint64_t)Z * (uint64_t)X - 1) <= 32;
+    const bool wide_val = dtype_size(dt) == 4;
+#define INSUM_MAP_CASE(KeyT, V)                                                                             \
+    return map_convert<KeyT, V>(b, X, Y, Z, nnz, mx, my, mz, mv, g, fill, num_groups, MAPZ, MAPX, MAPY, MAPV, \
+                                capacity_groups, s)
+    if (narrow && wide_val) INSUM_MAP_CASE(uint32_t, uint32_t);
+    if (narrow) INSUM_MAP_CASE(uint32_t, uint16_t);
+    if (wide_val) INSUM_MAP_CASE(uint64_t, uint32_t);
+    INSUM_MAP_CASE(uint64_t, uint16_t);
+#undef INSUM_MAP_CASE
 }

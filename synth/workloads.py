@@ -243,6 +243,12 @@ def make_config(name: str, seed: int = 0, shuffle: bool = True) -> dict:
         dt = "f32" if name == "cfg3" else "f16"    # the paper reports this experiment in both precisions
         row, col, val = zipf_rows_coo(M, K, 1.2, 16.0, seed, dt, "inv_deg", None, shuffle)
         cfg = dict(kind="group", M=M, K=K, N=N, a_dtype=dt, b_dtype=dt, c_dtype=dt)
+    elif name == "cfg3_wide":
+        # cfg3's generator with four times as many columns: B is 2 GiB, of which the 256 MB
+        # Infinity Cache can hold an eighth, so the gathers have to come from HBM itself.
+        M, K, N = 1 << 20, 1 << 22, 128
+        row, col, val = zipf_rows_coo(M, K, 1.2, 16.0, seed, "f32", "inv_deg", None, shuffle)
+        cfg = dict(kind="group", M=M, K=K, N=N, a_dtype="f32", b_dtype="f32", c_dtype="f32")
     elif name == "cfg4":  # 8192^2 bf16, 32x32 blocks, 10% of blocks, N=512
         M = K = 8192
         N = 512
