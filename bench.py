@@ -353,6 +353,45 @@ def group_size_sweep(torch, I, steps, warmup):
     return out
 
 
+def tail_cases(torch, I, steps, warmup):
+    """Two GroupCOO inputs that stress the parts of the SpMM outside its main loop, each timed
+    next to the time its bytes would take at the rate the same run measures on cfg3:
+    `hub`: rank-size row lengths (131072, 65536, ... entries: single rows span hundreds of work
+    ranges, whose partial sums the second kernel adds); `gaps`: 2^20 rows, nonzeros only in the
+    first and the last 1 % of them (98 % of C is zero-fill of rows without groups)."""
+    N, out = 128, {}
+    ref, _ = run_workload(torch, I, "cfg3", steps, warmup)
+    rate = ref["roofline"]["achieved"]                       # GB/s of real-entry bytes on cfg3
+    rng = np.random.default_rng(7)
+    cases = {}
+    M, K = 4096, 1 << 18
+    occ = np.minimum((K // 2) // np.arange(1, M + 1), K // 2).astype(np.int64)
+    occ[64:] = rng.integers(0, 4, M - 64)
+    row = np.repeat(np.arange(M, dtype=np.int32), occ)
+    col = np.concatenate([rng.choice(K, size=int(k), replace=False) for k in occ]).astype(np.int32)
+    cases["hub"] = (M, K, row, col)
+    M = K = 1 << 20
+    n = 8_000_000
+    r = rng.integers(0, M // 100, n)
+    r[n // 2:] = M - 1 - r[n // 2:]
+    cases["gaps"] = (M, K, r.astype(np.int32), rng.integers(0, K, n).astype(np.int32))
+    for name, (M, K, row, col) in cases.items():
+        val = torch.randn(row.size, device="cuda")
+        A = I.insum_coo_to_groupcoo(M, K, torch.from_numpy(row).cuda(), torch.from_numpy(col).cuda(), val, g=4)
+        B = torch.randn((K, N), device="cuda")
+        C = torch.empty((M, N), device="cuda")
+        ws = torch.empty(I.insum_spmm_groupcoo_workspace_bytes(M, N, A.G, A.g), dtype=torch.uint8, device="cuda")
+        ms = _time_launches(torch, lambda: I.insum_spmm_groupcoo(A, B, C_out=C, workspace=ws), steps, warmup)
+        nnz, slots = int(row.size), A.G * A.g
+        nbytes = nnz * (N * 4 + 8) + (slots - nnz) * 8 + 4 * A.G + M * N * 4
+        out[name] = {"M": M, "K": K, "N": N, "nnz": nnz, "ms": ms, "bytes": int(nbytes),
+                     "ms_at_cfg3_rate": nbytes / rate / 1e6, "ratio": ms / (nbytes / rate / 1e6)}
+        del A, B, C, ws
+        torch.cuda.empty_cache()
+    out["cfg3_rate_gbs"] = rate
+    return out
+
+
 def width_sweep(torch, I, steps, warmup):
     """GroupCOO SpMM on the cfg3 matrix for dense widths N = 8 ... 256 in fp32 and fp16: how the
     gather-bound kernel behaves from 16-byte to 1 KiB rows of B."""
@@ -475,6 +514,8 @@ def main():
                     help="only time the vendor libraries PyTorch dispatches to (context, not product)")
     ap.add_argument("--width-sweep", action="store_true",
                     help="only run the GroupCOO SpMM of cfg3 for N = 8 ... 256 in fp32 and fp16")
+    ap.add_argument("--tails", action="store_true",
+                    help="only time the hub-row and empty-row-gap inputs of the GroupCOO SpMM")
     ap.add_argument("--spconv", action="store_true",
                     help="only time the sparse-convolution workload (Section 6.4)")
     ap.add_argument("--peaks", action="store_true", help="only run the achievable-peak microbenchmarks")
@@ -506,6 +547,9 @@ def main():
         return
     if args.context:
         print(json.dumps({"vendor_context": vendor_context(torch, I, args.steps, args.warmup)}))
+        return
+    if args.tails:
+        print(json.dumps({"tail_cases": tail_cases(torch, I, args.steps, args.warmup)}))
         return
     if args.width_sweep:
         print(json.dumps({"width_sweep": width_sweep(torch, I, args.steps, args.warmup)}))

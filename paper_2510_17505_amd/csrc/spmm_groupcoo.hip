@@ -22,7 +22,10 @@
 //   * Scatter is a segment reduction: AM is non-decreasing, so the sub-wave keeps the row
 //     sum in registers while the row does not change and stores it once.  Rows between
 //     two stored rows have no groups; the sub-wave that sees the jump writes their zeros,
-//     so C needs no separate clearing pass.
+//     so C needs no separate clearing pass - except that of a long gap it only writes the
+//     ragged ends: the aligned 64-row chunks that lie wholly inside a gap are cleared, all in
+//     parallel, by extra workgroups at the front of the launch (a chunk is such a chunk exactly when
+//     no group's row falls into it: one binary search).
 //   * Rows cut by a run boundary: the piece at the head of a run and the piece at its
 //     tail go to an fp32 workspace; a second, tiny kernel adds the pieces of each such row
 //     in run order and writes the row once.  No floating-point atomics: results are
@@ -157,6 +160,8 @@ __device__ inline void store_partial(float* dst, const float (&acc)[E]) {
     for (int i = 0; i < E; ++i) dst[i] = acc[i];
 }
 
+constexpr int kGapChunk = 64;  // rows; aligned chunks inside a gap of empty rows are cleared by workgroups of their own
+
 template <typename TC, int E>
 __device__ inline void zero_rows(TC* C, int64_t ldc, int64_t n0, int64_t first, int64_t last_excl) {
     float z[E];
@@ -165,21 +170,84 @@ __device__ inline void zero_rows(TC* C, int64_t ldc, int64_t n0, int64_t first, 
     for (int64_t r = first; r < last_excl; ++r) store_c<TC, E>(C + r * ldc + n0, z, false);
 }
 
+// Rows [first, last_excl) have no groups.  Clears those of them that do not belong to an
+// aligned chunk of kGapChunk rows lying wholly inside the gap (at most 2 * (kGapChunk - 1) rows).
+template <typename TC, int E>
+__device__ inline void zero_gap_ends(TC* C, int64_t ldc, int64_t n0, int64_t first, int64_t last_excl) {
+    if (first >= last_excl) return;
+    const int64_t up = (first + kGapChunk - 1) / kGapChunk * kGapChunk;
+    const int64_t lo = up < last_excl ? up : last_excl;
+    const int64_t down = last_excl / kGapChunk * kGapChunk;
+    const int64_t hi = down > lo ? down : lo;
+    zero_rows<TC, E>(C, ldc, n0, first, lo);
+    zero_rows<TC, E>(C, ldc, n0, hi, last_excl);
+}
+
 __device__ inline int64_t group_of_slot(int64_t slot, int32_t g, int32_t g_shift) {
     return g_shift >= 0 ? (slot >> g_shift) : (slot / g);
 }
 
+__device__ inline int64_t first_group_at_or_after(const int32_t* __restrict__ AM, int64_t G, int64_t row) {
+    int64_t lo = 0, hi = G;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (AM[mid] < row) lo = mid + 1;
+        else hi = mid;
+    }
+    return lo;
+}
+
+// ---- chunks of empty rows ------------------------------------------------------------------------
+// A workgroup looks at kGapChunksPerBlock aligned chunks of kGapChunk rows: one thread per chunk
+// decides whether any group's row falls into it (binary search), then the whole workgroup
+// clears the chunks found empty, 16 bytes per lane where the layout allows.  These workgroups
+// travel at the front of the main launch.
+constexpr int kGapChunksPerBlock = 16;
+
+template <typename TC>
+__device__ inline void clear_empty_chunks(const GroupParams& p, int64_t chunk0) {
+    __shared__ int32_t empty[kGapChunksPerBlock];
+    if (threadIdx.x < kGapChunksPerBlock) {
+        const int64_t chunk = chunk0 + threadIdx.x;
+        bool is_empty = false;
+        if (chunk < p.M / kGapChunk) {
+            const int64_t q = first_group_at_or_after(p.AM, p.G, chunk * kGapChunk);
+            is_empty = q == p.G || p.AM[q] >= (chunk + 1) * kGapChunk;
+        }
+        empty[threadIdx.x] = is_empty;
+    }
+    __syncthreads();
+    TC* const C = static_cast<TC*>(p.C);
+    constexpr int V = 16 / (int)sizeof(TC);
+    const bool vec = p.N % V == 0 && p.ldc % V == 0 && (reinterpret_cast<uintptr_t>(C) % 16) == 0;
+    for (int c = 0; c < kGapChunksPerBlock; ++c) {
+        if (!empty[c]) continue;   // the same decision in every thread
+        TC* rows = C + (chunk0 + c) * kGapChunk * p.ldc;
+        if (vec) {
+            const int64_t per_row = p.N / V;
+            for (int r = 0; r < kGapChunk; ++r)
+                for (int64_t j = threadIdx.x; j < per_row; j += 256)
+                    __builtin_nontemporal_store(u32x4{0, 0, 0, 0}, reinterpret_cast<u32x4*>(rows + r * p.ldc) + j);
+        } else {
+            for (int r = 0; r < kGapChunk; ++r)
+                for (int64_t j = threadIdx.x; j < p.N; j += 256) rows[r * p.ldc + j] = from_float<TC>(0.f);
+        }
+    }
+}
+
 // ---- main kernel ---------------------------------------------------------------------
 template <typename TB, typename TC, int E, int SW>
-__global__ __launch_bounds__(256) void spmm_groupcoo_main(GroupParams p) {
+__global__ __launch_bounds__(256) void spmm_groupcoo_main(GroupParams p, unsigned gap_blocks) {
     constexpr int U = SW >= 8 ? 8 : SW;  // rows of B in flight per lane
+    if (blockIdx.x < gap_blocks) return clear_empty_chunks<TC>(p, (int64_t)blockIdx.x * kGapChunksPerBlock);
+    const unsigned block = blockIdx.x - gap_blocks;
     // Workgroup id = run block * col_tiles + column tile.  Consecutive ids go to different
     // XCDs, so with 8 (or 2, 4) column tiles every XCD keeps to its own columns of B and its
     // L2 holds a 1/8 slice instead of all of B.
     const int lane = threadIdx.x % SW;
-    const int64_t run = ((int64_t)(blockIdx.x / p.col_tiles) * 256 + threadIdx.x) / SW;
+    const int64_t run = ((int64_t)(block / p.col_tiles) * 256 + threadIdx.x) / SW;
     if (run >= p.runs) return;  // the SW lanes of a sub-wave leave together
-    const int64_t n0 = ((int64_t)(blockIdx.x % p.col_tiles) * SW + lane) * E;
+    const int64_t n0 = ((int64_t)(block % p.col_tiles) * SW + lane) * E;
     const bool col_ok = n0 < p.N;
 
     const TB* __restrict__ B = static_cast<const TB*>(p.B);
@@ -204,7 +272,7 @@ __global__ __launch_bounds__(256) void spmm_groupcoo_main(GroupParams p) {
     bool cur_is_head = prev_row == first_row;  // this row began in an earlier run
     float* const my_partial = p.partial + (run * 2) * p.npad + n0;
 
-    if (!accumulate && !cur_is_head && col_ok) zero_rows<TC, E>(C, p.ldc, n0, (int64_t)prev_row + 1, first_row);
+    if (!accumulate && !cur_is_head && col_ok) zero_gap_ends<TC, E>(C, p.ldc, n0, (int64_t)prev_row + 1, first_row);
 
     // Lanes beyond N (ragged last column tile) gather column 0 and never store.
     const TB* const Bcol = B + (col_ok ? n0 : 0);
@@ -227,7 +295,7 @@ __global__ __launch_bounds__(256) void spmm_groupcoo_main(GroupParams p) {
         if (col_ok) {
             if (cur_is_head) store_partial<E>(my_partial, acc);
             else store_c<TC, E>(C + (int64_t)cur * p.ldc + n0, acc, accumulate);
-            if (!accumulate) zero_rows<TC, E>(C, p.ldc, n0, (int64_t)cur + 1, next_row);
+            if (!accumulate) zero_gap_ends<TC, E>(C, p.ldc, n0, (int64_t)cur + 1, next_row);
         }
         cur_is_head = false;
         cur = next_row;
@@ -274,39 +342,101 @@ __global__ __launch_bounds__(256) void spmm_groupcoo_main(GroupParams p) {
         if (cur_is_head) store_partial<E>(my_partial, acc);
         else if (tail_cont) store_partial<E>(my_partial + p.npad, acc);
         else store_c<TC, E>(C + (int64_t)cur * p.ldc + n0, acc, accumulate);
-        if (ge == p.G && !accumulate) zero_rows<TC, E>(C, p.ldc, n0, (int64_t)cur + 1, p.M);
+        if (ge == p.G && !accumulate) zero_gap_ends<TC, E>(C, p.ldc, n0, (int64_t)cur + 1, p.M);
     }
 }
 
-// ---- rows shared between runs ----------------------------------------------------------
+// ---- rows shared between runs ------------------------------------------------------------------
 // Run r owns the row at its tail when that row starts inside r and continues into r+1.
-// Its sum is tail(r) + head(r+1) + head(r+2) + ... while the following runs still begin
-// with the same row.
+// Its sum is tail(r) + head(r+1) + ... + head(last), where `last`, the run that holds the row's
+// last group, comes from one binary search, so that the pieces are independent loads.
+// A row of up to kLongSpan pieces is added up by the sub-wave of its run.  A longer one (a hub
+// row) is added up by the whole workgroup: sub-wave j takes the pieces j, j + NSUB, ... and the
+// NSUB sums are combined in sub-wave order through LDS - a fixed order either way.
+constexpr int kLongSpan = 16;
+
+// acc += head(k) for k = first, first + stride, ... <= last, four loads in flight
+template <int E>
+__device__ inline void add_heads(const float* __restrict__ partial, int64_t npad, int64_t n0, int64_t first,
+                                 int64_t last, int64_t stride, float (&acc)[E]) {
+    int64_t k = first;
+    for (; k + 3 * stride <= last; k += 4 * stride) {
+        float piece[4][E];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int i = 0; i < E; ++i) piece[u][i] = partial[((k + u * stride) * 2) * npad + n0 + i];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int i = 0; i < E; ++i) acc[i] += piece[u][i];
+    }
+    for (; k <= last; k += stride) {
+#pragma unroll
+        for (int i = 0; i < E; ++i) acc[i] += partial[(k * 2) * npad + n0 + i];
+    }
+}
+
 template <typename TC, int E, int SW>
 __global__ __launch_bounds__(256) void spmm_groupcoo_seams(GroupParams p) {
-    const int lane = threadIdx.x % SW;
+    constexpr int NSUB = 256 / SW;
+    __shared__ int64_t long_run[NSUB], long_last[NSUB];   // hub rows owned by this workgroup's runs
+    __shared__ int32_t long_row[NSUB];
+    __shared__ float part[256 * E];
+    const int lane = threadIdx.x % SW, sub = threadIdx.x / SW;
     const int64_t run = ((int64_t)(blockIdx.x / p.col_tiles) * 256 + threadIdx.x) / SW;
-    if (run >= p.runs) return;
     const int64_t n0 = ((int64_t)(blockIdx.x % p.col_tiles) * SW + lane) * E;
-    if (n0 >= p.N) return;
+    const bool col_ok = n0 < p.N;
     const int32_t* __restrict__ AM = p.AM;
-    const int64_t gs = run * p.groups_per_run;
-    const int64_t ge = imin(p.G, gs + p.groups_per_run);
-    const int32_t row = AM[ge - 1];
-    if (!(ge < p.G && AM[ge] == row)) return;   // tail row ends here
-    if (gs > 0 && AM[gs - 1] == row) return;     // row began earlier: an earlier run owns it
-    float acc[E];
-    const float* tail = p.partial + (run * 2 + 1) * p.npad + n0;
-#pragma unroll
-    for (int i = 0; i < E; ++i) acc[i] = tail[i];
-    for (int64_t k = run + 1; k < p.runs; ++k) {
-        const float* head = p.partial + (k * 2) * p.npad + n0;
-#pragma unroll
-        for (int i = 0; i < E; ++i) acc[i] += head[i];
-        const int64_t ke = imin(p.G, (k + 1) * p.groups_per_run);
-        if (!(ke < p.G && AM[ke] == row)) break;
+    TC* const C = static_cast<TC*>(p.C);
+
+    bool owner = false;
+    int32_t row = 0;
+    int64_t last = 0;
+    if (run < p.runs) {
+        const int64_t gs = run * p.groups_per_run;
+        const int64_t ge = imin(p.G, gs + p.groups_per_run);
+        row = AM[ge - 1];
+        // the tail row goes on into the next run, and did not begin in an earlier one
+        owner = ge < p.G && AM[ge] == row && !(gs > 0 && AM[gs - 1] == row);
+        if (owner) last = (first_group_at_or_after(AM, p.G, (int64_t)row + 1) - 1) / p.groups_per_run;
     }
-    store_c<TC, E>(static_cast<TC*>(p.C) + (int64_t)row * p.ldc + n0, acc, p.accumulate != 0);
+    const bool is_long = owner && last - run > kLongSpan;
+    if (lane == 0) {
+        long_run[sub] = is_long ? run : -1;
+        long_last[sub] = last;
+        long_row[sub] = row;
+    }
+    if (owner && !is_long && col_ok) {
+        float acc[E];
+        const float* tail = p.partial + (run * 2 + 1) * p.npad + n0;
+#pragma unroll
+        for (int i = 0; i < E; ++i) acc[i] = tail[i];
+        add_heads<E>(p.partial, p.npad, n0, run + 1, last, 1, acc);
+        store_c<TC, E>(C + (int64_t)row * p.ldc + n0, acc, p.accumulate != 0);
+    }
+    __syncthreads();
+    for (int s = 0; s < NSUB; ++s) {
+        const int64_t r = long_run[s];   // the same in every thread
+        if (r < 0) continue;
+        float acc[E];
+#pragma unroll
+        for (int i = 0; i < E; ++i) acc[i] = 0.f;
+        if (col_ok) add_heads<E>(p.partial, p.npad, n0, r + 1 + sub, long_last[s], NSUB, acc);
+#pragma unroll
+        for (int i = 0; i < E; ++i) part[(sub * SW + lane) * E + i] = acc[i];
+        __syncthreads();
+        if (sub == 0 && col_ok) {
+            const float* tail = p.partial + (r * 2 + 1) * p.npad + n0;
+#pragma unroll
+            for (int i = 0; i < E; ++i) acc[i] = tail[i];
+            for (int j = 0; j < NSUB; ++j)
+#pragma unroll
+                for (int i = 0; i < E; ++i) acc[i] += part[(j * SW + lane) * E + i];
+            store_c<TC, E>(C + (int64_t)long_row[s] * p.ldc + n0, acc, p.accumulate != 0);
+        }
+        __syncthreads();
+    }
 }
 
 template <typename TC>
@@ -355,9 +485,12 @@ int64_t padded_cols(int64_t N) { return (N + 7) / 8 * 8; }
 
 template <typename TB, typename TC, int E, int SW>
 void launch_pair(const GroupParams& p, const Plan& pl, hipStream_t s) {
-    const dim3 grid((unsigned)(ceil_div(p.runs, 256 / SW) * pl.col_tiles));
-    hipLaunchKernelGGL((spmm_groupcoo_main<TB, TC, E, SW>), grid, dim3(256), 0, s, p);
-    hipLaunchKernelGGL((spmm_groupcoo_seams<TC, E, SW>), grid, dim3(256), 0, s, p);
+    const unsigned seam_blocks = (unsigned)(ceil_div(p.runs, 256 / SW) * pl.col_tiles);
+    // nothing to clear when C is accumulated into
+    const unsigned gap_blocks = p.accumulate ? 0u : (unsigned)ceil_div(p.M / kGapChunk, kGapChunksPerBlock);
+    hipLaunchKernelGGL((spmm_groupcoo_main<TB, TC, E, SW>), dim3(gap_blocks + seam_blocks), dim3(256), 0, s, p,
+                       gap_blocks);
+    hipLaunchKernelGGL((spmm_groupcoo_seams<TC, E, SW>), dim3(seam_blocks), dim3(256), 0, s, p);
 }
 
 template <typename TB, typename TC>

@@ -421,6 +421,35 @@ def test_spmm_groupcoo_hub_rows_large(I):
     assert_spmm_close(C.cpu().numpy(), C64, absprod, RTOL["f32"], "hub rows")
 
 
+@pytest.mark.parametrize("M,N,dtype", [(1 << 17, 128, "f32"), (100_003, 72, "f16"), (70_000, 33, "f32")])
+def test_spmm_groupcoo_long_runs_of_empty_rows(I, M, N, dtype):
+    """Nonzeros only in the first and the last 1 % of the rows plus a few isolated rows: nearly all
+    of C is zero-fill, most of it in aligned chunks that the second launch clears in parallel,
+    the ragged ends of every gap by the wavefront that sees the jump."""
+    K, g = 5000, 4
+    rng = np.random.default_rng(M % 1000)
+    lo = rng.integers(0, M // 100, 20_000)
+    hi = M - 1 - rng.integers(0, M // 100, 20_000)
+    lone = np.array([M // 3, M // 3 + 63, M // 3 + 64, M // 3 + 129, M // 2, M // 2 + 1000], dtype=np.int64)
+    row = np.concatenate([lo, hi, lone]).astype(np.int32)
+    col = rng.integers(0, K, row.size).astype(np.int32)
+    val = synth.round_to_dtype(rng.standard_normal(row.size), dtype)
+    _say(f"[spmm groupcoo gaps] M={M} N={N} {dtype} nnz={row.size}")
+    fmt = oracle.coo_to_groupcoo(M, K, row, col, synth.storage_array(val, dtype), g)
+    B = synth.round_to_dtype(np.random.default_rng(N).standard_normal((K, N)), dtype)
+    C64, absprod = _oracle_group_spmm(M, K, N, fmt, dtype, B)
+    A = _gpu_group_format(I, M, K, fmt, dtype)
+    C = torch.full((M, N), 3.0, dtype=TORCH_DTYPE[dtype], device="cuda")       # every element must be overwritten
+    I.insum_spmm_groupcoo(A, values_to_torch(B, dtype), C_out=C)
+    assert_spmm_close(C.float().cpu().numpy(), C64, absprod, RTOL[dtype], "gaps", out_dtype=dtype)
+    # accumulate: untouched rows keep their contents
+    C2 = torch.full((M, N), 3.0, dtype=TORCH_DTYPE[dtype], device="cuda")
+    I.insum_spmm_groupcoo(A, values_to_torch(B, dtype), C_out=C2, accumulate=True)
+    empty = np.ones(M, bool)
+    empty[row] = False
+    assert torch.all(C2[torch.from_numpy(empty).cuda()] == 3.0)
+
+
 def test_spmm_calls_can_be_captured_in_a_hip_graph(I):
     """Neither SpMM call allocates, synchronises or clears memory with a memset node, so a
     caller may capture it.  The graph is replayed several times with eager work in between and
