@@ -44,6 +44,10 @@ _lib.oracle_coo_to_blockgroupcoo.argtypes = [_i64, _i64, _i64, _p, _p, _p, C.c_i
                                              _i64, _i64, _p, _p, _i64, _p, _p, _p]
 _lib.oracle_spmm_groupcoo.restype = None
 _lib.oracle_spmm_groupcoo.argtypes = [_i64] * 5 + [_p, _p, _p, _p, _i64, _p, _i64]
+_lib.oracle_spmm_groupcoo_transposed.restype = None
+_lib.oracle_spmm_groupcoo_transposed.argtypes = [_i64] * 5 + [_p, _p, _p, _p, _i64, _p, _i64]
+_lib.oracle_enclosing_powers_of_two.restype = None
+_lib.oracle_enclosing_powers_of_two.argtypes = [_i64, _i64, _p, _p]
 _lib.oracle_spmm_blockgroupcoo.restype = None
 _lib.oracle_spmm_blockgroupcoo.argtypes = [_i64] * 7 + [_p, _p, _p, _p, _i64, _p, _i64]
 _lib.oracle_map_order.restype = C.c_int
@@ -102,6 +106,13 @@ def gstar(S: float, n: float) -> float:
 
 def default_group_size(S: int, n: int) -> int:
     return int(_lib.oracle_default_group_size(int(S), int(n)))
+
+
+def enclosing_powers_of_two(S: int, n: int):
+    """(lo, hi): the powers of two below and above g* = sqrt(S/n) (equal when g* is one itself)."""
+    lo, hi = C.c_int64(0), C.c_int64(0)
+    _lib.oracle_enclosing_powers_of_two(int(S), int(n), C.addressof(lo), C.addressof(hi))
+    return int(lo.value), int(hi.value)
 
 
 def coo_to_groupcoo(M, K, row, col, val, g=None):
@@ -182,6 +193,24 @@ def spmm_groupcoo(M, K, N, AM, AK, AV, B, C_init=None) -> np.ndarray:
         assert AM.min() >= 0 and AM.max() < M and AK.min() >= 0 and AK.max() < K
     _lib.oracle_spmm_groupcoo(M, K, N, G, g, _ptr(AM), _ptr(AK), _ptr(AV), _ptr(B), N, _ptr(Cd), N)
     return Cd
+
+
+def spmm_groupcoo_transposed(M, K, N, AM, AK, AV, E, D_init=None) -> np.ndarray:
+    """fp64 result of D[AK[p,q], n] += AV[p,q] * E[AM[p], n] (D = A^T E; starts at D_init or zero)."""
+    AM = np.ascontiguousarray(AM, dtype=np.int32)
+    AK = np.ascontiguousarray(AK, dtype=np.int32)
+    AV = _f32(AV)
+    E = _f32(E)
+    G = AM.shape[0]
+    g = AK.shape[1] if AK.ndim == 2 else 1
+    assert AK.size == G * g and AV.size == G * g and E.shape == (M, N)
+    Dd = np.zeros((K, N), dtype=np.float64) if D_init is None else \
+        np.array(D_init, dtype=np.float64, order="C")
+    assert Dd.shape == (K, N)
+    if G:
+        assert AM.min() >= 0 and AM.max() < M and AK.min() >= 0 and AK.max() < K
+    _lib.oracle_spmm_groupcoo_transposed(M, K, N, G, g, _ptr(AM), _ptr(AK), _ptr(AV), _ptr(E), N, _ptr(Dd), N)
+    return Dd
 
 
 def spmm_blockgroupcoo(M, K, N, bM, bK, AM, AK, AV, B, C_init=None) -> np.ndarray:

@@ -11,8 +11,9 @@
  *     figure captions;
  *   - the indirect-access count F(g), its relaxation and g* = sqrt(S/n):
  *     Section 4.2 "Choosing Group Size";
- *   - the SpMM loops: the "GroupCOO SpMM" listing of the ablation study (Section 6.5)
- *     and the BlockGroupCOO Einsum of Section 4.1;
+ *   - SpMM: the GroupCOO and BlockGroupCOO Einsums of Section 4.1, one update of the output
+ *     per stored slot; the product with the transposed matrix over the same format (the
+ *     derivative of the SpMM with respect to its dense operand, cf. Section 5.1);
  *   - point-cloud sparse convolution as an indirect Einsum grouped by kernel offset:
  *     Section 6.4 "Case Study: Point Cloud Sparse Convolution".
  *
@@ -102,6 +103,20 @@ int64_t oracle_default_group_size(int64_t S, int64_t n) {
         ++e;
     }
     return (int64_t)1 << e;
+}
+
+/* The two powers of two that enclose g* = sqrt(S/n) (Section 4.2: g* is rounded "to the nearest
+ * power-of-two values", plural, and the better of them is kept):  lo = 2^a with a the largest
+ * integer such that 4^a * n <= S (at least 1), hi = lo when g* is exactly lo, else 2 * lo. */
+void oracle_enclosing_powers_of_two(int64_t S, int64_t n, int64_t* lo, int64_t* hi) {
+    *lo = 1;
+    *hi = 1;
+    if (S <= 0 || n <= 0) return;
+    int a = 0;
+    while (a < 30 && ((__int128)n << (2 * (a + 1))) <= (__int128)S) ++a;
+    *lo = (int64_t)1 << a;
+    const __int128 at_lo = (__int128)n << (2 * a);
+    *hi = (at_lo >= (__int128)S) ? *lo : 2 * *lo;   /* S <= n * lo^2: g* <= lo (g* < 1 clamps to 1) */
 }
 
 /* ------------------------------------------------------------------------------------ */
@@ -270,7 +285,8 @@ static void column_slice(int64_t N, int64_t* n0, int64_t* n1) {
     *n1 = N * (t + 1) / T;
 }
 
-/* C[AM[p], n] += sum_q AV[p,q] * B[AK[p,q], n]   for every group p and column n.
+/* The GroupCOO Einsum of Section 4.1,  C[AM[p], n] += AV[p,q] * B[AK[p,q], n],  taken as it
+ * stands: one update of C per stored slot (p, q) and column n, slots in storage order.
  * C is not cleared here: the caller passes zeros (plain Einsum) or the matrix to
  * accumulate into.  Threads own disjoint column ranges, so there are no races and
  * the summation order per output element is fixed. */
@@ -283,13 +299,34 @@ void oracle_spmm_groupcoo(int64_t M, int64_t K, int64_t N, int64_t G, int64_t g,
     {
         int64_t n0, n1;
         column_slice(N, &n0, &n1);
-        for (int64_t p = 0; p < G; ++p) {
-            for (int64_t n = n0; n < n1; ++n) {
-                double acc = 0.0;
-                for (int64_t q = 0; q < g; ++q)
-                    acc += (double)AV[p * g + q] * (double)B[(int64_t)AK[p * g + q] * ldb + n];
-                C[(int64_t)AM[p] * ldc + n] += acc;
-            }
+        for (int64_t slot = 0; slot < G * g; ++slot) {
+            const double a = (double)AV[slot];
+            const float* brow = B + (int64_t)AK[slot] * ldb;
+            double* crow = C + (int64_t)AM[slot / g] * ldc;
+            for (int64_t n = n0; n < n1; ++n) crow[n] += a * (double)brow[n];
+        }
+    }
+}
+
+/* The same Einsum with the roles of the dense operands exchanged - the product with the
+ * transposed matrix over the same stored format, which is what differentiating the SpMM with
+ * respect to B gives (Section 5.1 names autodiff as a use of the Einsum form):
+ *     D[AK[p,q], n] += AV[p,q] * E[AM[p], n]        (D = A^T * E;  E is M x N, D is K x N)
+ * Slots in storage order, one update each.  D is not cleared here. */
+void oracle_spmm_groupcoo_transposed(int64_t M, int64_t K, int64_t N, int64_t G, int64_t g,
+                                     const int32_t* AM, const int32_t* AK, const float* AV,
+                                     const float* E, int64_t lde, double* D, int64_t ldd) {
+    (void)M;
+    (void)K;
+#pragma omp parallel
+    {
+        int64_t n0, n1;
+        column_slice(N, &n0, &n1);
+        for (int64_t slot = 0; slot < G * g; ++slot) {
+            const double a = (double)AV[slot];
+            const float* erow = E + (int64_t)AM[slot / g] * lde;
+            double* drow = D + (int64_t)AK[slot] * ldd;
+            for (int64_t n = n0; n < n1; ++n) drow[n] += a * (double)erow[n];
         }
     }
 }

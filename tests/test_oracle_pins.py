@@ -336,3 +336,70 @@ def test_scatter_and_gather_counts():
     assert (AM.size + AK.size) * N == oracle.indirect_access_cost(occ, g) * N
     _, AM1, AK1, _ = oracle.coo_to_groupcoo(M, K, row, col, val, 1)
     assert AM1.size * N == row.size * N
+
+
+# --------------------------------------------------------------------------- #
+# Section 4.2, last paragraph: the powers of two around g*
+# --------------------------------------------------------------------------- #
+def test_enclosing_powers_of_two():
+    # the paper's two cases (Section 6.5): g* = 20.2 lies between 16 and 32, g* = 3.58 between 2 and 4
+    assert oracle.enclosing_powers_of_two(1677722, 4096) == (16, 32)
+    assert oracle.enclosing_powers_of_two(1638, 128) == (2, 4)
+    assert oracle.enclosing_powers_of_two(16 * 7, 7) == (4, 4)      # g* = 4 exactly
+    assert oracle.enclosing_powers_of_two(3, 7) == (1, 1)           # g* < 1: group size 1
+    assert oracle.enclosing_powers_of_two(0, 5) == (1, 1)
+    rng = np.random.default_rng(0)
+    for _ in range(2000):
+        n = int(rng.integers(1, 1 << 20))
+        S = int(rng.integers(n, n << 12))                 # g* in [1, 64]
+        lo, hi = oracle.enclosing_powers_of_two(S, n)
+        # the definition, in rationals: lo^2 <= S/n <= hi^2, both powers of two, hi/lo in {1, 2}
+        assert lo & (lo - 1) == 0 and hi & (hi - 1) == 0 and hi in (lo, 2 * lo)
+        assert lo * lo * n <= S <= hi * hi * n
+        assert (hi == lo) == (lo * lo * n == S)
+        assert oracle.default_group_size(S, n) in (lo, hi)    # the nearest of the two in log2
+        gs = np.sqrt(S / n)
+        if abs(np.log2(gs) - round(np.log2(gs))) > 1e-9:      # away from exact powers: plain floats agree
+            assert lo == 2 ** int(np.floor(np.log2(gs))) and hi == 2 * lo
+
+
+# --------------------------------------------------------------------------- #
+# product with the transposed matrix over the same format
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("g", [1, 3, 4, 16])
+def test_spmm_groupcoo_transposed_equals_dense_gemm(g):
+    M, K, N = 23, 31, 7                                    # M != K != N: a swapped operand cannot pass
+    rng = np.random.default_rng(g)
+    row, col, val = synth.random_coo(M, K, 120, seed=g, dtype="f32")
+    E = rng.standard_normal((M, N)).astype(np.float32)
+    _, AM, AK, AV = oracle.coo_to_groupcoo(M, K, row, col, val, g)
+    D = oracle.spmm_groupcoo_transposed(M, K, N, AM, AK, AV, E)
+    A = coo_to_dense(M, K, row, col, val.astype(np.float64))
+    assert np.allclose(D, A.T @ E.astype(np.float64), rtol=1e-12, atol=1e-12)
+    # accumulating into an existing D
+    D0 = rng.standard_normal((K, N))
+    D2 = oracle.spmm_groupcoo_transposed(M, K, N, AM, AK, AV, E, D_init=D0)
+    assert np.allclose(D2, D0 + A.T @ E.astype(np.float64), rtol=1e-12, atol=1e-12)
+    # adjoint identity with the forward product: <A B, E> = <B, A^T E>
+    B = rng.standard_normal((K, N)).astype(np.float32)
+    C = oracle.spmm_groupcoo(M, K, N, AM, AK, AV, B)
+    assert np.isclose(np.sum(C * E), np.sum(B.astype(np.float64) * D), rtol=1e-11)
+
+
+def test_spmm_groupcoo_transposed_medium_against_scipy():
+    M, K, N = 3000, 2000, 48
+    row, col, val = synth.zipf_rows_coo(M, K, 1.2, 8.0, seed=2, dtype="f32", values="normal")
+    row = np.concatenate([row, row[:100]])                 # duplicates add up
+    col = np.concatenate([col, col[:100]])
+    val = np.concatenate([val, val[:100]])
+    E = np.random.default_rng(1).standard_normal((M, N)).astype(np.float32)
+    want = sp.csr_matrix((val.astype(np.float64), (row, col)), shape=(M, K)).T @ E.astype(np.float64)
+    for g in (1, 4, 7):
+        _, AM, AK, AV = oracle.coo_to_groupcoo(M, K, row, col, val, g)
+        D = oracle.spmm_groupcoo_transposed(M, K, N, AM, AK, AV, E)
+        assert np.allclose(D, want, rtol=1e-11, atol=1e-11)
+    # a padding slot's column does not matter (its value is zero)
+    _, AM, AK, AV = oracle.coo_to_groupcoo(M, K, row, col, val, 4)
+    AK2 = AK.copy()
+    AK2[AV == 0] = 0
+    assert np.allclose(oracle.spmm_groupcoo_transposed(M, K, N, AM, AK2, AV, E), want, rtol=1e-11, atol=1e-11)
