@@ -62,6 +62,40 @@ int32_t insum_default_group_size(int64_t S, int64_t n);
  * row occupancies.  Returns -1 for invalid arguments. */
 int64_t insum_indirect_access_cost(int64_t n, const int64_t* occ, int32_t g);
 
+/* The group sizes Section 4.2 considers for a matrix with S stored entries in n rows: the
+ * default above and its two power-of-two neighbours (so both powers of two that enclose g* are
+ * among them), ascending, at most three, written to out3.  Returns their number.  Host only. */
+int32_t insum_group_size_candidates(int64_t S, int64_t n, int32_t* out3);
+
+/* Bytes of device workspace insum_choose_group_size needs.  Host only. */
+size_t insum_choose_group_size_workspace_bytes(int64_t M, int64_t N, int64_t nnz, insum_dtype dt);
+
+/*
+ * Group size by measurement (Section 4.2: "round g* to the nearest power-of-two values and
+ * select the one with the best runtime").  For every candidate of
+ * insum_group_size_candidates(nnz, M) the COO matrix is converted to GroupCOO and
+ * insum_spmm_groupcoo is run on the caller's operands: one untimed launch, then `repeats`
+ * launches between two HIP events on `stream`.
+ *
+ *   row, col, val, dt   device; the matrix, as for insum_coo_to_groupcoo
+ *   B, ldb              device dt[K, ldb]; C, ldc, c_dt: device output, overwritten (C = A*B)
+ *   best_g              host out: the candidate with the smallest time per launch (the smaller
+ *                       one on a tie); the default group size when there is nothing to time
+ *   candidates, candidate_ms, num_candidates   host out, optional (NULL): what was tried and
+ *                       the milliseconds per launch of each (3 entries each)
+ *   workspace           device, at least insum_choose_group_size_workspace_bytes(...) bytes
+ *
+ * Synchronises the stream several times.  The formats it builds live in the workspace only:
+ * convert again with the chosen g.
+ */
+insum_status insum_choose_group_size(int64_t M, int64_t K, int64_t N, int64_t nnz,
+                                     const int32_t* row, const int32_t* col, const void* val,
+                                     insum_dtype dt, const void* B, int64_t ldb,
+                                     void* C, int64_t ldc, insum_dtype c_dt, int32_t repeats,
+                                     int32_t* best_g, int32_t* candidates, float* candidate_ms,
+                                     int32_t* num_candidates,
+                                     void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---------------------------------------------------------------------------------- */
 /* COO -> GroupCOO (Section 4.1, "Grouping")                                           */
 /* ---------------------------------------------------------------------------------- */

@@ -14,7 +14,9 @@ from .api import (  # noqa: F401
     MapGroupCOO,
     insum_coo_to_blockgroupcoo,
     insum_coo_to_groupcoo,
+    insum_choose_group_size,
     insum_default_group_size,
+    insum_group_size_candidates,
     insum_indirect_access_cost,
     insum_map_count_groups,
     insum_map_to_groupcoo,

@@ -39,6 +39,11 @@ _version = _sig("insum_version", C.c_int, [])
 _status_string = _sig("insum_status_string", C.c_char_p, [C.c_int])
 _default_g = _sig("insum_default_group_size", _i32, [_i64, _i64])
 _cost = _sig("insum_indirect_access_cost", _i64, [_i64, _p, _i32])
+_cand = _sig("insum_group_size_candidates", _i32, [_i64, _i64, _p])
+_choose_ws = _sig("insum_choose_group_size_workspace_bytes", C.c_size_t, [_i64, _i64, _i64, C.c_int])
+_choose = _sig("insum_choose_group_size", C.c_int,
+               [_i64, _i64, _i64, _i64, _p, _p, _p, C.c_int, _p, _i64, _p, _i64, C.c_int, _i32,
+                _p, _p, _p, _p, _p, C.c_size_t, _p])
 _g_ws = _sig("insum_coo_to_groupcoo_workspace_bytes", C.c_size_t, [_i64, _i64])
 _g_conv = _sig("insum_coo_to_groupcoo", C.c_int,
                [_i64, _i64, _i64, _p, _p, _p, C.c_int, _i32, _p, _p, _p, _p, _p, _i64,
@@ -114,6 +119,30 @@ def insum_default_group_size(S: int, n: int) -> int:
 def insum_indirect_access_cost(occ, g: int) -> int:
     arr = (C.c_int64 * len(occ))(*[int(x) for x in occ])
     return int(_cost(len(occ), C.cast(arr, _p), int(g)))
+
+
+def insum_group_size_candidates(S: int, n: int) -> list:
+    out = (C.c_int32 * 3)()
+    k = int(_cand(int(S), int(n), C.cast(out, _p)))
+    return [int(out[i]) for i in range(k)]
+
+
+def insum_choose_group_size(M: int, K: int, row, col, val, B: torch.Tensor, C_out: torch.Tensor | None = None,
+                            repeats: int = 5):
+    """Times the GroupCOO SpMM for the candidate group sizes of Section 4.2 on (row, col, val) x B.
+    Returns (best_g, {g: ms per launch})."""
+    row, col, val = _dev(row, "row"), _dev(col, "col"), _dev(val, "val")
+    assert B.is_cuda and B.dim() == 2 and B.shape[0] == K and B.stride(1) == 1 and B.dtype == val.dtype
+    N, nnz = B.shape[1], row.numel()
+    C_out = _out(C_out, M, N, B.dtype, B.device, False)
+    ws = torch.empty(int(_choose_ws(M, N, nnz, _DTYPE[val.dtype])), dtype=torch.uint8, device=B.device)
+    best, n = _i32(0), _i32(0)
+    cand, ms = (C.c_int32 * 3)(), (C.c_float * 3)()
+    _check(_choose(M, K, N, nnz, _ptr(row), _ptr(col), _ptr(val), _DTYPE[val.dtype], _ptr(B), B.stride(0),
+                   _ptr(C_out), C_out.stride(0), _DTYPE[C_out.dtype], int(repeats), C.addressof(best),
+                   C.cast(cand, _p), C.cast(ms, _p), C.addressof(n), _ptr(ws), ws.numel(), _stream()),
+           "insum_choose_group_size")
+    return best.value, {int(cand[i]): float(ms[i]) for i in range(n.value)}
 
 
 @dataclass

@@ -48,6 +48,24 @@ def test_host_entry_points():
     assert I.insum_indirect_access_cost([3, 1, 1, 2], 2) == 15
 
 
+def test_group_size_candidates():
+    """Section 4.2: the candidates hold the default and both powers of two around g*."""
+    I, _ = _lib()
+    assert I.insum_group_size_candidates(1677722, 4096) == [8, 16, 32]     # g* = 20.2 (Section 6.5)
+    assert I.insum_group_size_candidates(1638, 128) == [2, 4, 8]           # g* = 3.58
+    assert I.insum_group_size_candidates(3, 7) == [1, 2]
+    rng = np.random.default_rng(1)
+    for _ in range(500):
+        n = int(rng.integers(1, 1 << 20))
+        S = int(rng.integers(0, n << 12))
+        cand = I.insum_group_size_candidates(S, n)
+        lo, hi = oracle.enclosing_powers_of_two(S, n)
+        g0 = oracle.default_group_size(S, n)
+        assert cand == sorted(set(cand)) and 1 <= len(cand) <= 3
+        assert {lo, hi, g0} <= set(cand)
+        assert all(c & (c - 1) == 0 for c in cand)
+
+
 def test_argument_validation_without_a_gpu():
     """Calls that are rejected before any device work can be exercised on the CPU."""
     I, lib = _lib()
