@@ -317,40 +317,69 @@ def measured_peaks():
 
 
 def group_size_sweep(torch, I, steps, warmup):
-    """Section 4.2 / 6.5 experiment on the paper's ablation shape (4096 x 4096, 90 % sparsity in
-    32 x 32 blocks, fp16, N = 4096): time the SpMM kernels for a range of group sizes and report
-    the indirect-access count F(g) and the format size next to each time."""
+    """Section 4.2 / 6.5 experiment on the paper's two shapes - the ablation matrix (4096 x 4096,
+    90 % sparsity in 32 x 32 blocks) and the matrix of the runtime-versus-F(g) figure of Section 4.2
+    (the same at 80 % sparsity) - fp16, N = 4096: time both SpMM kernels for a range of group
+    sizes and report the indirect-access count F(g) and the format size next to each time, then
+    what insum_choose_group_size picks by timing the default and its neighbours."""
     import synth
     M = K = N = 4096
-    row, col, val = synth.random_block_coo(M, K, 32, 32, seed=0, dtype="f16", block_density=0.10,
-                                           sigma=0.02)
-    rd, cd = torch.from_numpy(row).cuda(), torch.from_numpy(col).cuda()
-    vd = _to_device(torch, val, "f16")
+    out = {}
     B = _to_device(torch, synth.round_to_dtype(
         np.random.default_rng(1).standard_normal((K, N)).astype(np.float32), "f16"), "f16")
     C = torch.empty((M, N), dtype=torch.float16, device="cuda")
-    flops = 2.0 * row.size * N
-    occ = np.bincount(row, minlength=M)
-    occ_b = np.bincount(np.unique((row // 32).astype(np.int64) * (K // 32) + col // 32) // (K // 32),
-                        minlength=M // 32)
-    out = {"shape": "4096x4096 fp16, 10 % of 32x32 blocks, N=4096", "nnz": int(row.size),
-           "default_g_rows": I.insum_default_group_size(int(row.size), M),
-           "default_g_block_rows": I.insum_default_group_size(int(occ_b.sum()), M // 32),
-           "groupcoo": [], "blockgroupcoo": []}
-    for g in (1, 2, 4, 8, 16, 32, 64, 128):
-        A = I.insum_coo_to_groupcoo(M, K, rd, cd, vd, g=g)
-        ws = torch.empty(I.insum_spmm_groupcoo_workspace_bytes(M, N, A.G, A.g), dtype=torch.uint8, device="cuda")
-        ms = _time_launches(torch, lambda: I.insum_spmm_groupcoo(A, B, C_out=C, workspace=ws), steps, warmup)
-        out["groupcoo"].append({"g": g, "ms": ms, "gflops": flops / ms / 1e6,
-                                "F": I.insum_indirect_access_cost(occ.tolist(), g),
-                                "format_bytes": int(A.AM.numel() * 4 + A.AK.numel() * 4 + A.AV.numel() * 2)})
-    for g in (1, 2, 4, 8, 16):
-        A = I.insum_coo_to_blockgroupcoo(M, K, rd, cd, vd, 32, 32, g=g)
-        ms = _time_launches(torch, lambda: I.insum_spmm_blockgroupcoo(A, B, C_out=C), steps, warmup)
-        out["blockgroupcoo"].append({"g": g, "ms": ms, "gflops": flops / ms / 1e6,
-                                     "F": I.insum_indirect_access_cost(occ_b.tolist(), g),
-                                     "format_bytes": int(A.AM.numel() * 4 + A.AK.numel() * 4 + A.AV.numel() * 2)})
+    for label, density in (("ablation_90pct_sparse", 0.10), ("fig_runtime_vs_F_80pct_sparse", 0.20)):
+        row, col, val = synth.random_block_coo(M, K, 32, 32, seed=0, dtype="f16", block_density=density,
+                                               sigma=0.02)
+        rd, cd = torch.from_numpy(row).cuda(), torch.from_numpy(col).cuda()
+        vd = _to_device(torch, val, "f16")
+        flops = 2.0 * row.size * N
+        occ = np.bincount(row, minlength=M)
+        occ_b = np.bincount(np.unique((row // 32).astype(np.int64) * (K // 32) + col // 32) // (K // 32),
+                            minlength=M // 32)
+        res = {"shape": f"4096x4096 fp16, {density:.0%} of 32x32 blocks, N=4096", "nnz": int(row.size),
+               "default_g_rows": I.insum_default_group_size(int(row.size), M),
+               "default_g_block_rows": I.insum_default_group_size(int(occ_b.sum()), M // 32),
+               "groupcoo": [], "blockgroupcoo": []}
+        for g in (1, 2, 4, 8, 16, 32, 64, 128):
+            A = I.insum_coo_to_groupcoo(M, K, rd, cd, vd, g=g)
+            ws = torch.empty(I.insum_spmm_groupcoo_workspace_bytes(M, N, A.G, A.g), dtype=torch.uint8, device="cuda")
+            ms = _time_launches(torch, lambda: I.insum_spmm_groupcoo(A, B, C_out=C, workspace=ws), steps, warmup)
+            res["groupcoo"].append({"g": g, "ms": ms, "gflops": flops / ms / 1e6,
+                                    "F": I.insum_indirect_access_cost(occ.tolist(), g),
+                                    "format_bytes": int(A.AM.numel() * 4 + A.AK.numel() * 4 + A.AV.numel() * 2)})
+        for g in (1, 2, 4, 8, 16, 32):
+            A = I.insum_coo_to_blockgroupcoo(M, K, rd, cd, vd, 32, 32, g=g)
+            ms = _time_launches(torch, lambda: I.insum_spmm_blockgroupcoo(A, B, C_out=C), steps, warmup)
+            res["blockgroupcoo"].append({"g": g, "ms": ms, "gflops": flops / ms / 1e6,
+                                         "F": I.insum_indirect_access_cost(occ_b.tolist(), g),
+                                         "format_bytes": int(A.AM.numel() * 4 + A.AK.numel() * 4 + A.AV.numel() * 2)})
+        best, times = I.insum_choose_group_size(M, K, rd, cd, vd, B, C_out=C, repeats=max(3, steps))
+        res["chosen_by_timing"] = {"g": best, "ms_per_candidate": times}
+        out[label] = res
+        del rd, cd, vd
+        torch.cuda.empty_cache()
     return out
+
+
+def run_transposed(torch, I, name, steps, warmup):
+    """D = A^T E over the stored GroupCOO format of workload `name` (E = the shape of that
+    workload's C): the derivative of the SpMM with respect to its dense operand."""
+    cfg, A, B, nnz, _ = prepare(torch, I, name)
+    M, K, N = cfg["M"], cfg["K"], cfg["N"]
+    dt = _torch_dtype(torch, cfg["c_dtype"])
+    E = torch.randn((M, N), device="cuda").to(dt)
+    D = torch.empty((K, N), dtype=dt, device="cuda")
+    nws = max(1, int(I.api._sgt_ws(K, N, I.api._DTYPE[dt])))
+    ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    ms = _time_launches(torch, lambda: I.insum_spmm_groupcoo_transposed(A, E, D_out=D, workspace=ws), steps, warmup)
+    s = SIZEOF[cfg["a_dtype"]]
+    # one row of E per group, one read-modify-write of a row of D (fp32 sums) per real entry
+    nbytes = A.G * (N * s + 4) + A.G * A.g * (4 + s) + nnz * N * 4 * 2 + K * N * s
+    return {"format": "GroupCOO (transposed product)", "dtype": cfg["a_dtype"], "nnz": nnz, "N": N, "g": A.g,
+            "ms_per_step": ms, "gflops": 2.0 * nnz * N / ms / 1e6, "model_gbs": nbytes / ms / 1e6,
+            "atomic_adds_per_s": nnz * N / ms * 1e3,
+            "note": "scatter with hardware fp32 atomic adds; bounded by the rate at which the L2 completes them"}
 
 
 def tail_cases(torch, I, steps, warmup):
@@ -599,6 +628,9 @@ def main():
             torch.cuda.empty_cache()
             others[name] = {k: r[k] for k in ("format", "dtype", "nnz", "N", "g", "ms_per_step", "gflops",
                                               "model_gbs", "roofline", "conversion_ms", "plan_ms") if k in r}
+        for name in ("cfg3", "cfg2"):
+            others[name + "_transposed"] = run_transposed(torch, I, name, args.steps, args.warmup)
+            torch.cuda.empty_cache()
         others["spconv"] = run_spconv(torch, I, args.steps, args.warmup)
         line["other_workloads"] = others
     if peaks is not None:

@@ -219,6 +219,40 @@ insum_status insum_spmm_groupcoo_noalloc(int64_t M, int64_t K, int64_t N, int64_
                                          void* stream);
 
 /* ---------------------------------------------------------------------------------- */
+/* Product with the transposed matrix over the same stored GroupCOO format             */
+/*     D[AK[p,q], n] += AV[p,q] * E[AM[p], n]          (D = A^T * E)                   */
+/* The Section 4.1 Einsum with the dense operands exchanged: the derivative of the     */
+/* SpMM with respect to B (Section 5.1 names autodiff as a use of the Einsum form).    */
+/* ---------------------------------------------------------------------------------- */
+
+/* Bytes of device workspace the call below needs: K x N fp32 sums when D is a 16-bit type,
+ * 0 when D is fp32.  Host only. */
+size_t insum_spmm_groupcoo_transposed_workspace_bytes(int64_t K, int64_t N, insum_dtype d_dt);
+
+/*
+ * D = A^T * E (accumulate == 0) or D += A^T * E, A (M x K) given in GroupCOO exactly as for
+ * insum_spmm_groupcoo - no second, transposed copy of A is needed.
+ *
+ *   E   device e_dt[M, lde], lde >= N;   D   device d_dt[K, ldd], ldd >= N
+ *   a_dt == e_dt in {F32, F16, BF16}; d_dt == e_dt or F32.
+ *   workspace   device, at least insum_spmm_groupcoo_transposed_workspace_bytes(...) bytes
+ *               (may be NULL when that is 0)
+ *
+ * A group's row of E is read once for its g slots; the contributions to a row of D are
+ * added in memory with hardware fp32 atomic adds (the format has no index by column).  So:
+ * products and sums are fp32, the order of the additions varies from run to run (results are
+ * reproducible up to fp32 summation order), a 16-bit D is summed in the fp32 workspace and
+ * rounded once, and with accumulate == 0 every element of D[0:K, 0:N] is written.  Slots with
+ * value zero contribute nothing; E is assumed finite.  Asynchronous.
+ */
+insum_status insum_spmm_groupcoo_transposed(int64_t M, int64_t K, int64_t N, int64_t G, int32_t g,
+                                            const int32_t* AM, const int32_t* AK, const void* AV,
+                                            insum_dtype a_dt,
+                                            const void* E, int64_t lde, insum_dtype e_dt,
+                                            void* D, int64_t ldd, insum_dtype d_dt, int accumulate,
+                                            void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------- */
 /* SpMM over BlockGroupCOO (Section 4.1, BlockGroupCOO Einsum)                         */
 /* ---------------------------------------------------------------------------------- */
 

@@ -7,6 +7,7 @@ in ``include/insum.h``.  Every step of the computation runs in the library's HIP
 there is no CPU or PyTorch fallback, and importing this package fails if the library can
 neither be loaded nor built.
 """
+from . import api  # noqa: F401
 from .api import (  # noqa: F401
     BlockGroupCOO,
     GroupCOO,
@@ -27,6 +28,7 @@ from .api import (  # noqa: F401
     insum_spmm_blockgroupcoo_workspace_bytes,
     insum_spmm_groupcoo,
     insum_spmm_groupcoo_noalloc,
+    insum_spmm_groupcoo_transposed,
     insum_spmm_groupcoo_workspace_bytes,
     insum_status_string,
     insum_version,

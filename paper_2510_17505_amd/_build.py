@@ -12,7 +12,7 @@ OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libinsum.so")
 PEAKS_LIB = os.path.join(PKG, "libinsum_peaks.so")   # achievable-peak microbenchmarks (bench.py --peaks)
 
-SOURCES = ["misc.cpp", "choose.cpp", "convert.hip", "spmm_groupcoo.hip", "spmm_blockgroupcoo.hip", "spconv_groupcoo.hip"]
+SOURCES = ["misc.cpp", "choose.cpp", "convert.hip", "spmm_groupcoo.hip", "spmm_groupcoo_transposed.hip", "spmm_blockgroupcoo.hip", "spconv_groupcoo.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -59,6 +59,10 @@ _sg = _sig("insum_spmm_groupcoo", C.c_int,
 _sg_na = _sig("insum_spmm_groupcoo_noalloc", C.c_int,
               [_i64, _i64, _i64, _i64, _i32, _p, _p, _p, C.c_int, _p, _i64, C.c_int,
                _p, _i64, C.c_int, C.c_int, _p])
+_sgt_ws = _sig("insum_spmm_groupcoo_transposed_workspace_bytes", C.c_size_t, [_i64, _i64, C.c_int])
+_sgt = _sig("insum_spmm_groupcoo_transposed", C.c_int,
+            [_i64, _i64, _i64, _i64, _i32, _p, _p, _p, C.c_int, _p, _i64, C.c_int,
+             _p, _i64, C.c_int, C.c_int, _p, C.c_size_t, _p])
 _sb_ws = _sig("insum_spmm_blockgroupcoo_workspace_bytes", C.c_size_t,
               [_i64, _i64, _i64, _i32, _i32, _i32])
 _sb = _sig("insum_spmm_blockgroupcoo", C.c_int,
@@ -282,6 +286,22 @@ def insum_spmm_groupcoo_noalloc(A: GroupCOO, B: torch.Tensor, C_out: torch.Tenso
                 _DTYPE[C_out.dtype], int(bool(accumulate)), _stream())
     _check(st, "insum_spmm_groupcoo_noalloc")
     return C_out
+
+
+def insum_spmm_groupcoo_transposed(A: GroupCOO, E: torch.Tensor, D_out: torch.Tensor | None = None,
+                                   accumulate: bool = False, out_dtype=None, workspace=None) -> torch.Tensor:
+    """D = A^T @ E (or D += A^T @ E) over the same GroupCOO arrays.  E: [M, N] row-major."""
+    assert E.is_cuda and E.dim() == 2 and E.shape[0] == A.M and E.stride(1) == 1
+    N = E.shape[1]
+    D_out = _out(D_out, A.K, N, out_dtype or E.dtype, E.device, accumulate)
+    nws = int(_sgt_ws(A.K, N, _DTYPE[D_out.dtype]))
+    if workspace is None and nws:
+        workspace = torch.empty(nws, dtype=torch.uint8, device=E.device)
+    st = _sgt(A.M, A.K, N, A.G, A.g, _ptr(A.AM), _ptr(A.AK), _ptr(A.AV), _DTYPE[A.AV.dtype],
+              _ptr(E), E.stride(0), _DTYPE[E.dtype], _ptr(D_out), D_out.stride(0), _DTYPE[D_out.dtype],
+              int(bool(accumulate)), _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream())
+    _check(st, "insum_spmm_groupcoo_transposed")
+    return D_out
 
 
 def insum_spmm_blockgroupcoo_plan(A: BlockGroupCOO, N: int) -> torch.Tensor | None:

@@ -487,17 +487,83 @@ def test_spmm_calls_can_be_captured_in_a_hip_graph(I):
         torch.cuda.synchronize()
 
 
-def test_backward_spmm_is_the_same_path_on_the_transposed_coordinates(I):
-    """dB = A^T dC (the gradient of C = A B with respect to B): converting the COO entries with
-    rows and columns swapped gives A^T in GroupCOO, and the same SpMM call does the rest.
-    Checked against a dense fp64 product, with fp32 output for fp16 operands."""
-    M, K, N = 900, 1300, 96
-    row, col, val = synth.zipf_rows_coo(M, K, 1.2, 10.0, seed=11, dtype="f16", values="normal")
-    dC = synth.round_to_dtype(np.random.default_rng(5).standard_normal((M, N)), "f16")
-    At = I.insum_coo_to_groupcoo(K, M, *coo_to_device(col, row, val, "f16"), g=0)      # K x M
-    dB = I.insum_spmm_groupcoo(At, values_to_torch(dC, "f16"), out_dtype=torch.float32)
-    A = np.zeros((M, K))
-    np.add.at(A, (row, col), val.astype(np.float64))
-    ref = A.T @ dC.astype(np.float64)
-    absprod = np.abs(A).T @ np.abs(dC).astype(np.float64)
-    assert_spmm_close(dB.cpu().numpy(), ref, absprod, RTOL["f16"], "A^T dC")
+TRANSPOSED_CASES = [
+    # M, K, N, nnz, g, dtype, kind, out32
+    (37, 53, 9, 300, 2, "f32", "uniform", False),        # scalar path
+    (3000, 2000, 128, 50000, 4, "f32", "zipf", False),   # cfg3 shape
+    (3000, 2000, 130, 50000, 4, "f32", "zipf", False),   # N not a multiple of 4
+    (1000, 4096, 256, 100000, 16, "f16", "uniform", False),
+    (1000, 4096, 256, 100000, 16, "bf16", "uniform", True),
+    (300, 100000, 64, 90000, 32, "f16", "hub", False),   # one long row of A = one row of E used 30 000 times
+    (4096, 64, 40, 30000, 7, "f32", "dups", False),      # few columns: every row of D receives ~500 atomics per element
+    (1000, 1000, 1032, 20000, 1, "f16", "uniform", True),    # several column tiles
+]
+
+
+@pytest.mark.parametrize("M,K,N,nnz,g,dtype,kind,out32", TRANSPOSED_CASES)
+def test_spmm_groupcoo_transposed_parity(I, M, K, N, nnz, g, dtype, kind, out32):
+    """D = A^T E over the same stored format (the derivative of the SpMM with respect to its dense
+    operand), against the oracle's fp64 Einsum with the dense operands exchanged."""
+    _say(f"[spmm groupcoo transposed] M={M} K={K} N={N} nnz~{nnz} g={g} {dtype} {kind}")
+    row, col, val = _group_case(M, K, nnz, kind, dtype, seed=N + g)
+    fmt = oracle.coo_to_groupcoo(M, K, row, col, synth.storage_array(val, dtype), g)
+    _, AM, AK, AV = fmt
+    av = to_f32(AV, dtype)
+    E = synth.round_to_dtype(np.random.default_rng(N).standard_normal((M, N)), dtype)
+    D0 = synth.round_to_dtype(np.random.default_rng(N + 1).standard_normal((K, N)), "f32" if out32 else dtype)
+    D64 = oracle.spmm_groupcoo_transposed(M, K, N, AM, AK, av, E)
+    absprod = oracle.spmm_groupcoo_transposed(M, K, N, AM, AK, np.abs(av), np.abs(E))
+    A = _gpu_group_format(I, M, K, fmt, dtype)
+    Ed = values_to_torch(E, dtype)
+    odt = torch.float32 if out32 else TORCH_DTYPE[dtype]
+    D = torch.full((K, N), 5.0, dtype=odt, device="cuda")            # must be overwritten everywhere
+    I.insum_spmm_groupcoo_transposed(A, Ed, D_out=D)
+    assert_spmm_close(D.float().cpu().numpy(), D64, absprod, RTOL[dtype], "D=A^T E",
+                      out_dtype=None if out32 else dtype)
+    Dacc = values_to_torch(D0, "f32" if out32 else dtype)
+    I.insum_spmm_groupcoo_transposed(A, Ed, D_out=Dacc, accumulate=True)
+    assert_spmm_close(Dacc.float().cpu().numpy(), D64 + D0.astype(np.float64), absprod + np.abs(D0), RTOL[dtype],
+                      "D+=A^T E", out_dtype=None if out32 else dtype)
+
+
+def test_spmm_groupcoo_transposed_is_the_gradient_of_the_forward_product(I):
+    """<A B, E> = <B, A^T E> with both sides from the library (fp32), and strided operands."""
+    M, K, N, g = 900, 1300, 96, 4
+    row, col, val = synth.zipf_rows_coo(M, K, 1.2, 10.0, seed=11, dtype="f32", values="normal")
+    A = I.insum_coo_to_groupcoo(M, K, *coo_to_device(row, col, val, "f32"), g=g)
+    rng = np.random.default_rng(5)
+    Bw = torch.from_numpy(rng.standard_normal((K, N + 32)).astype(np.float32)).cuda()
+    Ew = torch.from_numpy(rng.standard_normal((M, N + 8)).astype(np.float32)).cuda()
+    B, E = Bw[:, :N], Ew[:, :N]
+    C = I.insum_spmm_groupcoo(A, B)
+    Dw = torch.full((K, N + 4), 7.0, device="cuda")
+    I.insum_spmm_groupcoo_transposed(A, E, D_out=Dw[:, :N])
+    lhs = float((C.double() * E.double()).sum())
+    rhs = float((B.double() * Dw[:, :N].double()).sum())
+    assert abs(lhs - rhs) <= 1e-5 * float((C.double().abs() * E.double().abs()).sum())
+    assert torch.all(Dw[:, N:] == 7.0)
+    # empty format: D = 0, or D unchanged when accumulating
+    A0 = I.GroupCOO(M, K, 4, torch.zeros(0, dtype=torch.int32, device="cuda"),
+                    torch.zeros((0, 4), dtype=torch.int32, device="cuda"), torch.zeros((0, 4), device="cuda"))
+    assert torch.all(I.insum_spmm_groupcoo_transposed(A0, E.contiguous()) == 0)
+
+
+def test_choose_group_size_times_the_neighbours(I):
+    """Section 4.2: the candidates are timed on the caller's operands; the chosen g is one of
+    them, and converting with it gives the oracle's format and product."""
+    M, K, N = 4096, 4096, 256
+    row, col, val = synth.random_coo(M, K, 400_000, seed=2, dtype="f16", sigma=0.02)    # g* ~ 9.9
+    rd, cd, vd = coo_to_device(row, col, val, "f16")
+    B = synth.round_to_dtype(np.random.default_rng(3).standard_normal((K, N)), "f16")
+    Bd = values_to_torch(B, "f16")
+    best, times = I.insum_choose_group_size(M, K, rd, cd, vd, Bd, repeats=5)
+    cand = I.insum_group_size_candidates(row.size, M)
+    _say(f"[choose g] candidates {cand} ms {times} -> {best}")
+    assert cand == [4, 8, 16] and sorted(times) == cand and best in cand
+    assert all(t > 0 for t in times.values()) and times[best] == min(times.values())
+    fmt = oracle.coo_to_groupcoo(M, K, row, col, synth.storage_array(val, "f16"), best)
+    A = I.insum_coo_to_groupcoo(M, K, rd, cd, vd, g=best)
+    assert_format_equal(A.g, A.AM, A.AK, A.AV, fmt)
+    C64, absprod = _oracle_group_spmm(M, K, N, fmt, "f16", B)
+    assert_spmm_close(I.insum_spmm_groupcoo(A, Bd).float().cpu().numpy(), C64, absprod, RTOL["f16"], "chosen g",
+                      out_dtype="f16")
