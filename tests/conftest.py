@@ -10,6 +10,8 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # pytest-timeout registers this mark itself when it is installed; without it the mark is inert
+    config.addinivalue_line("markers", "timeout(seconds): time limit of a test (pytest-timeout)")
 
 
 def pytest_collection_modifyitems(config, items):

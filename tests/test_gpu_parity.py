@@ -269,7 +269,7 @@ SPMM_BLOCK_CASES = [
     (512, 1024, 128, 64, 32, 3, "bf16", 0.3),
     (256, 512, 72, 32, 16, 4, "bf16", 0.5),
     (256, 1024, 320, 32, 128, 2, "f16", 0.5),     # two k-chunks per block
-    (256, 768, 64, 64, 48, 4, "bf16", 0.5),       # bK = 48 -> 16-wide k-chunks
+    (256, 768, 64, 64, 48, 4, "bf16", 0.5),       # bK = 48 is not a multiple of 32 -> general kernel
     (2048, 2048, 512, 32, 32, 4, "bf16", 0.1),    # cfg4 shape, smaller
     (2048, 2048, 1024, 64, 64, 4, "bf16", 0.05),  # cfg5 shape, smaller; empty block rows
     (96, 160, 40, 8, 16, 3, "f32", 0.4),          # general kernel
@@ -323,6 +323,30 @@ def test_spmm_blockgroupcoo_accumulate_and_f32_out(I, bM, bK, N):
     C64b, absb = _oracle_block_spmm(M, K, N, bM, bK, fmt, dtype, B)
     Cf = I.insum_spmm_blockgroupcoo(A, Bw[:, :N], out_dtype=torch.float32)
     assert_spmm_close(Cf.cpu().numpy(), C64b, absb, RTOL[dtype], "f32 out")
+
+
+@pytest.mark.parametrize("bM,bK,N", [(32, 32, 256), (8, 8, 40)])
+def test_spmm_blockgroupcoo_repeated_block_column_is_taken_as_padding(I, bM, bK, N):
+    """The precondition stated in the header: among the real slots of a block row the block
+    columns are strictly increasing, and a slot that repeats the column of the slot before it in
+    its group is padding.  A hand-built format that breaks it (a repeated column with nonzero
+    values) is therefore multiplied as if that slot were zero - on both kernels."""
+    M, K, g, dtype = 2 * bM, 6 * bK, 3, "bf16"
+    rng = np.random.default_rng(bM)
+    AM = np.array([0, 1], dtype=np.int32)
+    AK = np.array([[1, 4, 4], [0, 2, 5]], dtype=np.int32)          # group 0 repeats block column 4
+    AV = synth.round_to_dtype(rng.standard_normal((2, g, bM, bK)) * 0.5, dtype)
+    B = synth.round_to_dtype(rng.standard_normal((K, N)), dtype)
+    A = I.BlockGroupCOO(M, K, bM, bK, g, torch.from_numpy(AM).cuda(), torch.from_numpy(AK).cuda(),
+                        values_to_torch(AV, dtype))
+    got = I.insum_spmm_blockgroupcoo(A, values_to_torch(B, dtype)).float().cpu().numpy()
+    as_padding = AV.copy()
+    as_padding[0, 2] = 0.0
+    C64 = oracle.spmm_blockgroupcoo(M, K, N, bM, bK, AM, AK, as_padding, B)
+    absprod = oracle.spmm_blockgroupcoo(M, K, N, bM, bK, AM, AK, np.abs(as_padding), np.abs(B))
+    assert_spmm_close(got, C64, absprod, RTOL[dtype], "repeated column skipped")
+    literal = oracle.spmm_blockgroupcoo(M, K, N, bM, bK, AM, AK, AV, B)   # the Einsum taken literally
+    assert np.abs(literal - C64).max() > 0.1                              # ... differs: hence the precondition
 
 
 def _hub_block_coo(nbr, nbc, bM, bK, occ, seed, dtype):

@@ -266,6 +266,32 @@ def test_spconv_full_size_properties_and_samples():
     assert np.all(err <= 1e-5 * abssum), float((err / abssum).max())
 
 
+def test_spconv_full_size_every_element():
+    """The benchmark workload again, every element of Out against the oracle run over the whole
+    map (about 75 GFLOP of fp64 loops on the host cores: the slow one of the two full-size tests)."""
+    P, mx, my, mz, mv = synth.voxel_kernel_map(96, 0.3, seed=0, dtype="f16")
+    C = M = 128
+    In = _features(P, C, 1, "f16")
+    W = synth.round_to_dtype(_features(C, M, 2, "f16", lead=27) * np.float32(0.125), "f16")
+    st = synth.storage_array(mv, "f16")
+    g, MZ, MX, MY, MV = oracle.map_to_groupcoo(P, P, 27, mx, my, mz, st, None)
+    Map = I.insum_map_to_groupcoo(P, P, 27, _i32(mx), _i32(my), _i32(mz), values_to_torch(mv, "f16"))
+    assert Map.g == g and np.array_equal(Map.MAPZ.cpu().numpy(), MZ)
+    assert np.array_equal(Map.MAPX.cpu().numpy(), MX) and np.array_equal(Map.MAPY.cpu().numpy(), MY)
+    print(f"[spconv full] P={P} entries={mx.size} g={g}: oracle over the whole map ...", flush=True)
+    mvf = MV.astype(np.float32)
+    want = oracle.spconv_groupcoo(P, C, M, MZ, MX, MY, mvf, In, W)
+    absprod = oracle.spconv_groupcoo(P, C, M, MZ, MX, MY, np.abs(mvf), np.abs(In), np.abs(W))
+    print("[spconv full] library ...", flush=True)
+    Ind, Wd = values_to_torch(In, "f16"), values_to_torch(W, "f16")
+    ws = torch.empty(max(1, I.insum_spconv_groupcoo_workspace_bytes(Map, C, M, Ind.dtype)), dtype=torch.uint8,
+                     device="cuda")
+    got = I.insum_spconv_groupcoo(Map, Ind, Wd, workspace=ws)
+    assert_spmm_close(got.cpu().numpy(), want, absprod, RTOL, "whole output")
+    again = I.insum_spconv_groupcoo(Map, Ind, Wd, workspace=ws, reuse_map_tables=True)
+    assert_spmm_close(again.cpu().numpy(), want, absprod, RTOL, "whole output, tables reused")
+
+
 @pytest.mark.parametrize("values", ["ones", "normal"])
 def test_spconv_reuses_the_map_tables_across_layers(values):
     """Three layers over one kernel map: the later calls skip the table build and must still
