@@ -348,12 +348,12 @@ __global__ __launch_bounds__(256) void spmm_groupcoo_main(GroupParams p, unsigne
 
 // ---- rows shared between runs ------------------------------------------------------------------
 // Run r owns the row at its tail when that row starts inside r and continues into r+1.
-// Its sum is tail(r) + head(r+1) + ... + head(last), where `last`, the run that holds the row's
-// last group, comes from one binary search, so that the pieces are independent loads.
+// Its sum is tail(r) + head(r+1) + ... + head(last), where `last` is the run that holds the row's
+// last group (for a long row found by binary search), so that the pieces are independent loads.
 // A row of up to kLongSpan pieces is added up by the sub-wave of its run.  A longer one (a hub
 // row) is added up by the whole workgroup: sub-wave j takes the pieces j, j + NSUB, ... and the
 // NSUB sums are combined in sub-wave order through LDS - a fixed order either way.
-constexpr int kLongSpan = 16;
+constexpr int kLongSpan = 8;
 
 // acc += head(k) for k = first, first + stride, ... <= last, four loads in flight
 template <int E>
@@ -399,7 +399,26 @@ __global__ __launch_bounds__(256) void spmm_groupcoo_seams(GroupParams p) {
         row = AM[ge - 1];
         // the tail row goes on into the next run, and did not begin in an earlier one
         owner = ge < p.G && AM[ge] == row && !(gs > 0 && AM[gs - 1] == row);
-        if (owner) last = (first_group_at_or_after(AM, p.G, (int64_t)row + 1) - 1) / p.groups_per_run;
+        if (owner) {
+            // Most shared rows end in the next run or two: look at the first group of the next
+            // kLongSpan + 2 runs (independent loads), and search only when the row is still going on.
+            int32_t begins[kLongSpan + 1];   // row at the start of run + 2 + k (-1 past the end)
+#pragma unroll
+            for (int k = 0; k <= kLongSpan; ++k) {
+                const int64_t ke = (run + 2 + k) * p.groups_per_run;
+                begins[k] = ke < p.G ? AM[ke] : -1;
+            }
+            bool ended = false;
+            last = run + kLongSpan + 2;
+#pragma unroll
+            for (int k = kLongSpan; k >= 0; --k) {
+                if (begins[k] != row) {
+                    ended = true;
+                    last = run + 1 + k;
+                }
+            }
+            if (!ended) last = (first_group_at_or_after(AM, p.G, (int64_t)row + 1) - 1) / p.groups_per_run;
+        }
     }
     const bool is_long = owner && last - run > kLongSpan;
     if (lane == 0) {
