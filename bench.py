@@ -196,7 +196,8 @@ def run_workload(torch, I, name, steps, warmup, peaks=None):
                               "gather repeats the row just fetched and is not counted)"}
         if peaks:
             row_bytes = N * sB
-            key = "2GiB" if b_bytes > (256 << 20) else "128MiB" if b_bytes > (32 << 20) else None
+            key = ("2GiB" if b_bytes > (512 << 20) else "512MiB" if b_bytes > (128 << 20) else
+                   "128MiB" if b_bytes > (32 << 20) else None)       # the measured set nearest to B's size
             mp = peaks.get("random_row_read_gbs", {}).get(str(row_bytes), {}).get(key) if key else None
             if mp:
                 roof["measured_peak"] = mp
@@ -223,12 +224,16 @@ def run_workload(torch, I, name, steps, warmup, peaks=None):
         if peaks:
             # The format fixes bM flop per gathered byte of B (a gathered tile serves the bM rows of
             # one block); B tiles that miss L2 arrive at the measured rate of L2-missing reads.
-            beyond_l2 = peaks.get("random_1kib_read_gbs", {}).get("128MiB")
-            if beyond_l2:
-                bound = min(MFMA_PEAK_TFLOPS, cfg["bM"] * beyond_l2 / 1e3)
+            # The rate is the one measured for random 1 KiB reads over a working set of B's size class
+            # (B decides how many of the gathers hit L2).
+            key = ("1MiB" if b_bytes <= (1 << 20) else "16MiB" if b_bytes <= (16 << 20) else
+                   "128MiB" if b_bytes <= (128 << 20) else "2GiB")
+            rate = peaks.get("random_1kib_read_gbs", {}).get(key)
+            if rate:
+                bound = min(MFMA_PEAK_TFLOPS, cfg["bM"] * rate / 1e3)
                 roof["bound_tflops"] = bound
-                roof["bound_is"] = (f"min(MFMA peak, bM = {cfg['bM']} flop/byte x {beyond_l2:.0f} GB/s of "
-                                    f"L2-missing 1 KiB reads measured on this chip)")
+                roof["bound_is"] = (f"min(MFMA peak, bM = {cfg['bM']} flop/byte x {rate:.0f} GB/s of random 1 KiB "
+                                    f"reads over a {key} set measured on this chip; B is {b_bytes >> 20} MiB)")
                 roof["frac_of_bound"] = tf / bound
             if peaks.get("mfma_bf16_tflops"):
                 roof["measured_peak"] = peaks["mfma_bf16_tflops"]
@@ -302,7 +307,7 @@ def measured_peaks():
                        ("insum_peak_mfma_tflops", [ctypes.c_int])):
         getattr(lib, name).restype = ctypes.c_double
         getattr(lib, name).argtypes = args
-    sets = (("128MiB", 128 << 20), ("2GiB", 2 << 30))
+    sets = (("128MiB", 128 << 20), ("512MiB", 512 << 20), ("2GiB", 2 << 30))
     return {
         "stream_copy_gbs": lib.insum_peak_copy_gbs(2 << 30, 3),
         "stream_read_gbs": lib.insum_peak_read_gbs(2 << 30, 3),
