@@ -48,7 +48,61 @@ def test_random_groupcoo_problem(seed):
     else:
         C = values_to_torch(C0, dtype)
         I.insum_spmm_groupcoo(A, Bd, C_out=C, accumulate=True)
-    assert_spmm_close(C.float().cpu().numpy(), C64, absprod, RTOL[dtype], f"seed {seed}")
+    assert_spmm_close(C.float().cpu().numpy(), C64, absprod, RTOL[dtype], f"seed {seed}", out_dtype=dtype)
+    # the product with the transposed matrix over the same arrays
+    E = synth.round_to_dtype(rng.standard_normal((M, N)), dtype)
+    D64 = oracle.spmm_groupcoo_transposed(M, K, N, AM, AK, av, E)
+    absD = oracle.spmm_groupcoo_transposed(M, K, N, AM, AK, np.abs(av), np.abs(E))
+    D = I.insum_spmm_groupcoo_transposed(A, values_to_torch(E, dtype),
+                                         out_dtype=torch.float32 if seed % 2 else None)
+    assert_spmm_close(D.float().cpu().numpy(), D64, absD, RTOL[dtype], f"transposed, seed {seed}",
+                      out_dtype=None if seed % 2 else dtype)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_skewed_block_rows_with_and_without_plan(seed):
+    """Block rows of very different lengths (one holds hundreds of blocks, some none): with a
+    plan the long one is split into chunks, without it one workgroup walks it."""
+    import paper_2510_17505_amd as I
+    rng = np.random.default_rng(4000 + seed)
+    bM, bK = [(32, 32), (64, 32), (32, 64), (64, 64)][seed % 4]
+    nbr = int(rng.integers(1, 7))
+    nbc = int(rng.integers(300, 700))
+    N = int(rng.choice([8, 64, 136, 256, 264, 520]))
+    g = int(rng.choice([1, 2, 3, 4, 8, 70]))
+    dtype = ["bf16", "f16"][seed % 2]
+    occ = rng.integers(0, 6, nbr)
+    occ[int(rng.integers(0, nbr))] = int(rng.integers(150, nbc))
+    M, K = nbr * bM, nbc * bK
+    print(f"[random skewed blocks] seed={seed} b={bM}x{bK} rows={occ.tolist()} N={N} g={g} {dtype}", flush=True)
+    AMl, AKl, AVl = [], [], []
+    for r, k in enumerate(occ):
+        if k == 0:
+            continue
+        cols = np.sort(rng.choice(nbc, size=int(k), replace=False))
+        ng = -(-int(k) // g)
+        ak = np.concatenate([cols, np.full(ng * g - k, cols[-1])]).reshape(ng, g)
+        av = synth.round_to_dtype(rng.standard_normal((ng, g, bM, bK)) * 0.5, dtype)
+        av.reshape(ng * g, bM, bK)[int(k):] = 0.0
+        AMl += [r] * ng
+        AKl.append(ak)
+        AVl.append(av)
+    AM = np.array(AMl, dtype=np.int32)
+    AK = np.concatenate(AKl).astype(np.int32)
+    AV = np.concatenate(AVl)
+    B = synth.round_to_dtype(rng.standard_normal((K, N)), dtype)
+    C64 = oracle.spmm_blockgroupcoo(M, K, N, bM, bK, AM, AK, AV, B)
+    absprod = oracle.spmm_blockgroupcoo(M, K, N, bM, bK, AM, AK, np.abs(AV), np.abs(B))
+    A = I.BlockGroupCOO(M, K, bM, bK, g, torch.from_numpy(AM).cuda(), torch.from_numpy(AK).cuda(),
+                        values_to_torch(AV, dtype))
+    Bd = values_to_torch(B, dtype)
+    planned = I.insum_spmm_blockgroupcoo(A, Bd)
+    assert_spmm_close(planned.float().cpu().numpy(), C64, absprod, RTOL[dtype], f"planned, seed {seed}",
+                      out_dtype=dtype)
+    assert torch.equal(planned, I.insum_spmm_blockgroupcoo(A, Bd))
+    unplanned = I.insum_spmm_blockgroupcoo(A, Bd, plan=False)
+    assert_spmm_close(unplanned.float().cpu().numpy(), C64, absprod, RTOL[dtype], f"unplanned, seed {seed}",
+                      out_dtype=dtype)
 
 
 @pytest.mark.parametrize("seed", range(30))
