@@ -157,7 +157,11 @@ size_t insum_coo_to_blockgroupcoo_workspace_bytes(int64_t M, int64_t K, int64_t 
  * ordered by (block row, block column) and grouped like the entries of GroupCOO;
  * padding blocks are all +0 and repeat the last real block column of their group.
  * The same (row, col) given twice is INSUM_ERR_DUPLICATE.
- * Count mode and capacity behaviour as for insum_coo_to_groupcoo.
+ * Count mode and capacity behaviour as for insum_coo_to_groupcoo.  A count call leaves its
+ * sorted entries in the workspace; a fill call with the same arguments (sizes, pointers, dtype,
+ * block shape) and the same workspace goes on from them instead of sorting again, so between
+ * such a pair neither the workspace nor row / col / val may be modified.  The fill call
+ * consumes them: a second fill call sorts afresh.
  */
 insum_status insum_coo_to_blockgroupcoo(int64_t M, int64_t K, int64_t nnz,
                                         const int32_t* row, const int32_t* col, const void* val,
