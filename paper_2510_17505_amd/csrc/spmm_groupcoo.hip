@@ -489,13 +489,22 @@ Plan make_plan(int64_t N, int64_t G, int32_t g, int elem_size, bool vec, int64_t
         pl.SW = chunks <= 16 ? 16 : 64;
     }
     pl.col_tiles = ceil_div(chunks, pl.SW);
-    // About two runs per sub-wave slot of the chip (256 CUs x 32 wavefronts), but never
-    // fewer than two SW-slot batches per run.
+    // At most two runs per sub-wave slot of the chip (256 CUs x 32 wavefronts), never fewer than
+    // two SW-slot batches per run.  A run also costs a start-up (its rows' bounds from AM, the
+    // first batch of slots) and two partial rows for the seam pass, which weigh on runs of a few
+    // batches: runs grow towards 256 slots as long as half of the chip's sub-wave slots still get
+    // one (cfg2: 64 -> 224 slots per run, 63 -> 56 us; the large workloads are unaffected).
     const int64_t subwaves = 256LL * 32 * (64 / pl.SW);
     int64_t target_runs = std::max<int64_t>(1, 2 * subwaves / pl.col_tiles);
     if (run_cap > 0) target_runs = std::min(target_runs, run_cap);
     const int64_t min_groups = std::max<int64_t>(1, ceil_div(2 * pl.SW, g));
-    pl.groups_per_run = std::max<int64_t>(min_groups, ceil_div(G, target_runs));
+    int64_t gpr = std::max<int64_t>(min_groups, ceil_div(G, target_runs));
+    const int64_t preferred = std::max<int64_t>(min_groups, ceil_div(256, g));
+    if (gpr < preferred) {
+        const int64_t half_chip = std::max<int64_t>(1, subwaves / 2 / pl.col_tiles);
+        gpr = std::min(preferred, std::max(gpr, ceil_div(G, half_chip)));
+    }
+    pl.groups_per_run = gpr;
     pl.runs = G > 0 ? ceil_div(G, pl.groups_per_run) : 0;
     return pl;
 }
