@@ -71,8 +71,8 @@ int32_t insum_group_size_candidates(int64_t S, int64_t n, int32_t* out3);
 size_t insum_choose_group_size_workspace_bytes(int64_t M, int64_t N, int64_t nnz, insum_dtype dt);
 
 /*
- * Group size by measurement (Section 4.2: "round g* to the nearest power-of-two values and
- * select the one with the best runtime").  For every candidate of
+ * Group size by measurement (Section 4.2, last paragraph: the powers of two next to g* are
+ * tried and the fastest is kept).  For every candidate of
  * insum_group_size_candidates(nnz, M) the COO matrix is converted to GroupCOO and
  * insum_spmm_groupcoo is run on the caller's operands: one untimed launch, then `repeats`
  * launches between two HIP events on `stream`.
