@@ -138,6 +138,40 @@ def coo_to_groupcoo(M, K, row, col, val, g=None):
     return int(g), AM, AK, AV
 
 
+def groupcoo_real_slots(AK, AV) -> np.ndarray:
+    """Boolean [G, g]: which slots of a GroupCOO matrix hold entries.  Section 4.1 pads the last
+    group of a row; by this build's reading a padding slot has value +0 (all bits zero) and
+    repeats the column of the slot to its left, so padding is recognised from the arrays alone:
+    slot q > 0 is padding when its value bits are zero and AK[p, q] == AK[p, q - 1].  (A stored
+    +0 entry that repeats the coordinate of the entry before it looks the same and is treated
+    the same; it contributes nothing to any product.)"""
+    AK = np.asarray(AK)
+    bits = np.ascontiguousarray(AV).view({2: np.uint16, 4: np.uint32}[np.asarray(AV).dtype.itemsize])
+    real = np.ones(AK.shape, dtype=bool)
+    G, g = AK.shape
+    for p_ in range(G):
+        for q in range(1, g):
+            real[p_, q] = not (bits[p_, q] == 0 and AK[p_, q] == AK[p_, q - 1])
+    return real
+
+
+def groupcoo_transpose(M, K, AM, AK, AV, g_t=None):
+    """GroupCOO of A^T (K rows, M columns) from the GroupCOO of A: the entries of A, read off the
+    format in slot order with padding left out, with row and column exchanged, grouped again as
+    Section 4.1 prescribes.  Returns (g_t, AM_t, AK_t, AV_t)."""
+    AM, AK, AV = np.asarray(AM), np.asarray(AK), np.ascontiguousarray(AV)
+    real = groupcoo_real_slots(AK, AV)
+    rows, cols, vals = [], [], []
+    for p_ in range(AK.shape[0]):
+        for q in range(AK.shape[1]):
+            if real[p_, q]:
+                rows.append(AK[p_, q])      # the column of A is the row of A^T
+                cols.append(AM[p_])
+                vals.append(AV[p_, q])
+    return coo_to_groupcoo(K, M, np.array(rows, dtype=np.int32), np.array(cols, dtype=np.int32),
+                           np.array(vals, dtype=AV.dtype), g_t)
+
+
 def coo_to_blockgroupcoo(M, K, row, col, val, bM, bK, g=None):
     """Returns (g, AM[G], AK[G,g], AV[G,g,bM,bK]); AM/AK hold block coordinates."""
     row, col = _coords(row, col)

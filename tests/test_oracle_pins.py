@@ -403,3 +403,68 @@ def test_spmm_groupcoo_transposed_medium_against_scipy():
     AK2 = AK.copy()
     AK2[AV == 0] = 0
     assert np.allclose(oracle.spmm_groupcoo_transposed(M, K, N, AM, AK2, AV, E), want, rtol=1e-11, atol=1e-11)
+
+
+# --------------------------------------------------------------------------- #
+# GroupCOO of the transposed matrix, built from the format
+# --------------------------------------------------------------------------- #
+def test_real_slots_by_hand():
+    AK = np.array([[2, 5, 5], [7, 7, 7], [1, 1, 4], [3, 3, 3]], dtype=np.int32)
+    AV = np.array([[1, 2, 0], [3, 0, 0], [0, 5, 6], [0, 0, 9]], dtype=np.float32)
+    want = np.array([[1, 1, 0], [1, 0, 0],
+                     [1, 1, 1],            # a zero in slot 0 is an entry; the repeated column carries 5
+                     [1, 0, 1]], dtype=bool)   # a +0 repeat is dropped, the nonzero repeat after it is kept
+    assert np.array_equal(oracle.groupcoo_real_slots(AK, AV), want)
+    AVn = AV.copy()
+    AVn[1, 1] = -0.0                       # -0 is not the padding pattern
+    assert oracle.groupcoo_real_slots(AK, AVn)[1, 1]
+    # 16-bit values
+    assert np.array_equal(oracle.groupcoo_real_slots(AK, AV.astype(np.float16)), want)
+
+
+@pytest.mark.parametrize("g,g_t", [(1, 1), (4, 4), (3, 5), (16, 2)])
+def test_groupcoo_transpose_is_the_format_of_the_transposed_matrix(g, g_t):
+    M, K = 37, 23                                          # M != K
+    row, col, val = synth.zipf_rows_coo(M, K, 1.2, 4.0, seed=g, dtype="f32", values="normal")
+    row = np.concatenate([row, row[:9]])                   # repeated coordinates stay separate entries
+    col = np.concatenate([col, col[:9]])
+    val = np.concatenate([val, 2 * val[:9]])
+    _, AM, AK, AV = oracle.coo_to_groupcoo(M, K, row, col, val, g)
+    assert int(oracle.groupcoo_real_slots(AK, AV).sum()) == row.size
+    gt, AMt, AKt, AVt = oracle.groupcoo_transpose(M, K, AM, AK, AV, g_t)
+    assert gt == g_t
+    # the matrix it holds is the transpose, value for value
+    A = coo_to_dense(M, K, row, col, val.astype(np.float64))
+    assert np.array_equal(groupcoo_to_dense(K, M, AMt, AKt, AVt.astype(np.float64)), A.T)
+    # and it is a valid GroupCOO of the exchanged coordinates (structure checked independently)
+    check_groupcoo_invariants(K, M, col, row, val, g_t, AMt, AKt, AVt)
+    # the same arrays as converting the exchanged COO directly: entries with equal coordinates
+    # keep their order, because the format stores them in input order
+    _, AMd, AKd, AVd = oracle.coo_to_groupcoo(K, M, col, row, val, g_t)
+    assert np.array_equal(AMt, AMd) and np.array_equal(AKt, AKd)
+    assert np.array_equal(AVt.view(np.uint32), AVd.view(np.uint32))
+
+
+def test_groupcoo_transpose_twice_is_the_identity():
+    M, K = 50, 64
+    row, col, val = synth.random_coo(M, K, 400, seed=5, dtype="f16")
+    val = synth.storage_array(val, "f16")
+    g, AM, AK, AV = oracle.coo_to_groupcoo(M, K, row, col, val, 4)
+    _, AMt, AKt, AVt = oracle.groupcoo_transpose(M, K, AM, AK, AV, 8)
+    g2, AM2, AK2, AV2 = oracle.groupcoo_transpose(K, M, AMt, AKt, AVt, 4)
+    assert g2 == g and np.array_equal(AM2, AM) and np.array_equal(AK2, AK)
+    assert np.array_equal(AV2.view(np.uint16), AV.view(np.uint16))
+    # default group size: the Section 4.2 rule on the entries and the rows of A^T
+    gd, *_ = oracle.groupcoo_transpose(M, K, AM, AK, AV)
+    assert gd == oracle.default_group_size(400, K)
+
+
+def test_groupcoo_transpose_product_agrees_with_the_transposed_product():
+    M, K, N = 40, 30, 5
+    row, col, val = synth.random_coo(M, K, 300, seed=8, dtype="f32")
+    E = np.random.default_rng(0).standard_normal((M, N)).astype(np.float32)
+    _, AM, AK, AV = oracle.coo_to_groupcoo(M, K, row, col, val, 4)
+    _, AMt, AKt, AVt = oracle.groupcoo_transpose(M, K, AM, AK, AV, 4)
+    D1 = oracle.spmm_groupcoo_transposed(M, K, N, AM, AK, AV, E)
+    D2 = oracle.spmm_groupcoo(K, M, N, AMt, AKt, AVt, E)
+    assert np.allclose(D1, D2, rtol=1e-12, atol=1e-12)
