@@ -386,23 +386,21 @@ def run_transposed(torch, I, name, steps, warmup):
            "atomic_adds_per_s": nnz * N / ms * 1e3,
            "note": "scatter with hardware fp32 atomic adds; bounded by the rate at which the L2 completes them"}
     # The other route to the same product, for a matrix that is used many times (training): a
-    # second GroupCOO copy holding A^T (one more conversion, rows and columns exchanged), then the
-    # ordinary SpMM - no atomics, a fixed summation order.
-    del A, ws
-    row = torch.from_numpy(cfg["col"]).cuda()
-    col = torch.from_numpy(cfg["row"]).cuda()
-    val = _to_device(torch, cfg["val"], cfg["a_dtype"])
+    # second GroupCOO copy holding A^T (insum_groupcoo_transpose: built once from the format), then
+    # the ordinary SpMM - no atomics, a fixed summation order.
+    del ws
     conv_ms = None
     for _ in range(2):
         At = None
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        At = I.insum_coo_to_groupcoo(K, M, row, col, val, g=0)
+        At = I.insum_groupcoo_transpose(A)
         torch.cuda.synchronize()
         conv_ms = (time.perf_counter() - t0) * 1e3
+    del A
     ws = torch.empty(max(1, I.insum_spmm_groupcoo_workspace_bytes(K, N, At.G, At.g)), dtype=torch.uint8, device="cuda")
     ms2 = _time_launches(torch, lambda: I.insum_spmm_groupcoo(At, E, C_out=D, workspace=ws), steps, warmup)
-    out["via_second_copy_of_A_transposed"] = {"conversion_ms": conv_ms, "g": At.g, "ms_per_step": ms2,
+    out["via_second_copy_of_A_transposed"] = {"transpose_ms": conv_ms, "g": At.g, "ms_per_step": ms2,
                                               "gflops": 2.0 * nnz * N / ms2 / 1e6}
     return out
 

@@ -135,6 +135,42 @@ insum_status insum_coo_to_groupcoo(int64_t M, int64_t K, int64_t nnz,
                                    int32_t* AM, int32_t* AK, void* AV, int64_t capacity_groups,
                                    void* workspace, size_t workspace_bytes, void* stream);
 
+/* Bytes of device workspace insum_groupcoo_transpose needs.  Host only; 0 for invalid sizes. */
+size_t insum_groupcoo_transpose_workspace_bytes(int64_t M, int64_t K, int64_t G, int32_t g);
+
+/*
+ * GroupCOO of A^T (K rows, M columns) from the GroupCOO of A: a second, column-grouped copy of
+ * the matrix, for callers that multiply by A^T many times (the backward pass of a layer whose
+ * forward pass is the Section 4.1 SpMM).  insum_spmm_groupcoo on the result computes A^T * E
+ * without atomics and in a fixed summation order, several times faster than
+ * insum_spmm_groupcoo_transposed on the original arrays.
+ *
+ *   AM, AK, AV, dt, G, g   device; the format of A as produced by insum_coo_to_groupcoo
+ *   g_t        group size of the result, or 0 for insum_default_group_size(entries, K)
+ *   g_used, num_groups      host out, as for insum_coo_to_groupcoo
+ *   num_entries             host out, optional (NULL): entries found in the format
+ *   AM_t, AK_t, AV_t, capacity_groups   device outputs, as for insum_coo_to_groupcoo
+ *                           (num_groups never exceeds entries/g_t + min(K, entries), and
+ *                           entries <= G * g); all NULL = count mode
+ *   workspace  device, at least insum_groupcoo_transpose_workspace_bytes(M, K, G, g) bytes
+ *
+ * The entries are read off the format in slot order with row and column exchanged and grouped
+ * again by the rule of insum_coo_to_groupcoo (so entries with the same coordinates keep their
+ * order).  Padding is recognised by the pattern that conversion writes: a slot other than the
+ * first of its group whose value bits are all zero and whose column equals that of the slot to
+ * its left.  A stored +0 entry that repeats the coordinates of the entry before it has the same
+ * pattern and is left out with the padding; no product changes by that.
+ * Statuses as for insum_coo_to_groupcoo (INSUM_ERR_OUT_OF_RANGE for an AM outside [0, M) or an
+ * AK outside [0, K)); G * g must be below 2^31.  Synchronises `stream`.
+ */
+insum_status insum_groupcoo_transpose(int64_t M, int64_t K, int64_t G, int32_t g,
+                                      const int32_t* AM, const int32_t* AK, const void* AV,
+                                      insum_dtype dt, int32_t g_t,
+                                      int32_t* g_used, int64_t* num_groups, int64_t* num_entries,
+                                      int32_t* AM_t, int32_t* AK_t, void* AV_t,
+                                      int64_t capacity_groups,
+                                      void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---------------------------------------------------------------------------------- */
 /* COO -> BlockGroupCOO (Section 4.1, "Group+Blocking")                                */
 /* ---------------------------------------------------------------------------------- */

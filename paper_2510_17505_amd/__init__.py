@@ -17,6 +17,7 @@ from .api import (  # noqa: F401
     insum_coo_to_groupcoo,
     insum_choose_group_size,
     insum_default_group_size,
+    insum_groupcoo_transpose,
     insum_group_size_candidates,
     insum_indirect_access_cost,
     insum_map_count_groups,

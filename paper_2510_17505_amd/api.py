@@ -48,6 +48,10 @@ _g_ws = _sig("insum_coo_to_groupcoo_workspace_bytes", C.c_size_t, [_i64, _i64])
 _g_conv = _sig("insum_coo_to_groupcoo", C.c_int,
                [_i64, _i64, _i64, _p, _p, _p, C.c_int, _i32, _p, _p, _p, _p, _p, _i64,
                 _p, C.c_size_t, _p])
+_gt_ws = _sig("insum_groupcoo_transpose_workspace_bytes", C.c_size_t, [_i64, _i64, _i64, _i32])
+_gt = _sig("insum_groupcoo_transpose", C.c_int,
+           [_i64, _i64, _i64, _i32, _p, _p, _p, C.c_int, _i32, _p, _p, _p, _p, _p, _p, _i64,
+            _p, C.c_size_t, _p])
 _b_ws = _sig("insum_coo_to_blockgroupcoo_workspace_bytes", C.c_size_t, [_i64, _i64, _i64, _i32, _i32])
 _b_conv = _sig("insum_coo_to_blockgroupcoo", C.c_int,
                [_i64, _i64, _i64, _p, _p, _p, C.c_int, _i32, _i32, _i32, _p, _p, _p, _p, _p, _i64,
@@ -219,6 +223,23 @@ def insum_coo_to_groupcoo(M: int, K: int, row, col, val, g: int = 0) -> GroupCOO
         g_used.value = g_eff
     AM, AK, AV = AM[:G.value], AK[:G.value], AV[:G.value]
     return GroupCOO(M, K, g_used.value, AM, AK, AV)
+
+
+def insum_groupcoo_transpose(A: GroupCOO, g: int = 0) -> GroupCOO:
+    """GroupCOO of A^T built on the device from the GroupCOO of A (count call, then fill call)."""
+    dev = A.AV.device
+    ws = torch.empty(max(1, int(_gt_ws(A.M, A.K, A.G, A.g))), dtype=torch.uint8, device=dev)
+    g_used, G, entries = _i32(0), _i64(0), _i64(0)
+    args = (A.M, A.K, A.G, A.g, _ptr(A.AM), _ptr(A.AK), _ptr(A.AV), _DTYPE[A.AV.dtype], int(g),
+            C.addressof(g_used), C.addressof(G), C.addressof(entries))
+    _check(_gt(*args, 0, 0, 0, 0, _ptr(ws), ws.numel(), _stream()), "insum_groupcoo_transpose(count)")
+    AM = torch.empty(G.value, dtype=torch.int32, device=dev)
+    AK = torch.empty((G.value, g_used.value), dtype=torch.int32, device=dev)
+    AV = torch.empty((G.value, g_used.value), dtype=A.AV.dtype, device=dev)
+    if G.value:
+        _check(_gt(*args, _ptr(AM), _ptr(AK), _ptr(AV), G.value, _ptr(ws), ws.numel(), _stream()),
+               "insum_groupcoo_transpose(fill)")
+    return GroupCOO(A.K, A.M, g_used.value, AM, AK, AV)
 
 
 def insum_coo_to_blockgroupcoo(M: int, K: int, row, col, val, bM: int, bK: int, g: int = 0) -> BlockGroupCOO:

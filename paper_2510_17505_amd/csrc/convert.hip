@@ -168,6 +168,37 @@ __global__ void k_group_fill(Divisor per_row, int64_t nnz, int32_t g, const KeyT
     }
 }
 
+// ---- kernels: GroupCOO -> COO of the transposed matrix ------------------------------------------
+// A slot holds an entry unless it is padding: value bits all zero and the column of the slot to
+// its left (same group) repeated - the pattern the conversion above writes.
+template <typename V>
+__device__ inline bool slot_is_real(const int32_t* __restrict__ AK, const V* __restrict__ AV, int64_t i, int32_t g) {
+    return i % g == 0 || AV[i] != (V)0 || AK[i] != AK[i - 1];
+}
+
+// real[i] = 1 for a slot with an entry, for i < slots; real[slots] = 0 (the scan's total)
+template <typename V>
+__global__ void k_real_slots(int64_t slots, int32_t g, const int32_t* __restrict__ AK, const V* __restrict__ AV,
+                             int32_t* __restrict__ real) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i > slots) return;
+    real[i] = i < slots && slot_is_real(AK, AV, i, g) ? 1 : 0;
+}
+
+// entry number offs[i] of the transposed matrix: (row, col, value) = (AK[i], AM[i / g], AV[i])
+template <typename V>
+__global__ void k_transposed_entries(int64_t slots, int32_t g, const int32_t* __restrict__ AM,
+                                     const int32_t* __restrict__ AK, const V* __restrict__ AV,
+                                     const int32_t* __restrict__ offs, int32_t* __restrict__ row,
+                                     int32_t* __restrict__ col, V* __restrict__ val) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= slots || !slot_is_real(AK, AV, i, g)) return;
+    const int32_t e = offs[i];
+    row[e] = AK[i];
+    col[e] = AM[i / g];
+    val[e] = AV[i];
+}
+
 // ---- kernels: BlockGroupCOO ----------------------------------------------------------------
 template <typename KeyT>
 __global__ void k_block_keys(int64_t M, int64_t K, int64_t nnz, int32_t bM, int32_t bK,
@@ -610,6 +641,89 @@ extern "C" insum_status insum_coo_to_groupcoo(int64_t M, int64_t K, int64_t nnz,
     if (wide_val) INSUM_GROUP_CASE(uint64_t, uint32_t);
     INSUM_GROUP_CASE(uint64_t, uint16_t);
 #undef INSUM_GROUP_CASE
+}
+
+// ============================================================================================
+namespace {
+
+struct TransposeBuffers {
+    int32_t *real, *offs, *row, *col;
+    void* val;
+    void* scan_temp;
+    size_t scan_bytes;
+};
+
+size_t transpose_front_bytes(int64_t slots) {   // everything ahead of the conversion's own workspace
+    const size_t n1 = (size_t)std::max<int64_t>(slots, 1);
+    return 256 + 2 * align_up((n1 + 1) * 4, 256) + 3 * align_up(n1 * 4, 256) +
+           align_up(scan_temp_bytes(slots + 1), 256);
+}
+
+bool carve_transpose(Carver& ws, TransposeBuffers& t, int64_t slots) {
+    t.real = ws.take<int32_t>(slots + 1);
+    t.offs = ws.take<int32_t>(slots + 1);
+    t.row = ws.take<int32_t>(slots);
+    t.col = ws.take<int32_t>(slots);
+    t.val = ws.take<int32_t>(slots);   // values are at most 4 bytes wide
+    t.scan_bytes = scan_temp_bytes(slots + 1);
+    t.scan_temp = ws.take<char>(t.scan_bytes);
+    return ws.ok;
+}
+
+// the entries of A^T as COO arrays in the workspace; *nnz = their number (synchronises)
+template <typename V>
+insum_status transposed_entries(const TransposeBuffers& t, int64_t slots, int32_t g, const int32_t* AM,
+                                const int32_t* AK, const void* AV, int64_t* nnz, hipStream_t s) {
+    const V* av = static_cast<const V*>(AV);
+    hipLaunchKernelGGL(k_real_slots<V>, dim3(blocks_for(slots + 1)), dim3(kThreads), 0, s, slots, g, AK, av, t.real);
+    INSUM_HIP_TRY(hipGetLastError());
+    const insum_status st = scan_exclusive(t.scan_temp, t.scan_bytes, t.real, t.offs, slots + 1, s);
+    if (st != INSUM_OK) return st;
+    hipLaunchKernelGGL(k_transposed_entries<V>, dim3(blocks_for(slots)), dim3(kThreads), 0, s, slots, g, AM, AK, av,
+                       t.offs, t.row, t.col, static_cast<V*>(t.val));
+    INSUM_HIP_TRY(hipGetLastError());
+    int32_t total = 0;
+    INSUM_HIP_TRY(hipMemcpyAsync(&total, t.offs + slots, sizeof(total), hipMemcpyDeviceToHost, s));
+    INSUM_HIP_TRY(hipStreamSynchronize(s));
+    *nnz = total;
+    return INSUM_OK;
+}
+
+}  // namespace
+
+extern "C" size_t insum_groupcoo_transpose_workspace_bytes(int64_t M, int64_t K, int64_t G, int32_t g) {
+    if (M < 0 || K < 0 || G < 0 || g <= 0 || G * (int64_t)g >= (1LL << 31)) return 0;
+    const int64_t slots = G * (int64_t)g;
+    return transpose_front_bytes(slots) + insum_coo_to_groupcoo_workspace_bytes(K, slots);
+}
+
+extern "C" insum_status insum_groupcoo_transpose(int64_t M, int64_t K, int64_t G, int32_t g, const int32_t* AM,
+                                                 const int32_t* AK, const void* AV, insum_dtype dt, int32_t g_t,
+                                                 int32_t* g_used, int64_t* num_groups, int64_t* num_entries,
+                                                 int32_t* AM_t, int32_t* AK_t, void* AV_t,
+                                                 int64_t capacity_groups, void* workspace,
+                                                 size_t workspace_bytes, void* stream) {
+    if (M < 0 || K < 0 || G < 0 || g <= 0 || g_t < 0 || !g_used || !num_groups) return INSUM_ERR_INVALID_ARG;
+    if (M >= (1LL << 31) || K >= (1LL << 31) || G * (int64_t)g >= (1LL << 31)) return INSUM_ERR_INVALID_ARG;
+    if (!dtype_valid(dt)) return INSUM_ERR_INVALID_ARG;
+    if (G > 0 && (!AM || !AK || !AV)) return INSUM_ERR_INVALID_ARG;
+    const int64_t slots = G * (int64_t)g;
+    int64_t nnz = 0;
+    Carver ws(workspace, workspace_bytes);
+    TransposeBuffers t{};
+    if (slots > 0) {
+        if (!carve_transpose(ws, t, slots)) return INSUM_ERR_CAPACITY;
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        const insum_status st = dtype_size(dt) == 4
+                                    ? transposed_entries<uint32_t>(t, slots, g, AM, AK, AV, &nnz, s)
+                                    : transposed_entries<uint16_t>(t, slots, g, AM, AK, AV, &nnz, s);
+        if (st != INSUM_OK) return st;
+    }
+    if (num_entries) *num_entries = nnz;
+    // the rest of the workspace serves the conversion of the exchanged coordinates
+    const uintptr_t rest = std::min(ws.cur, ws.end);
+    return insum_coo_to_groupcoo(K, M, nnz, t.row, t.col, t.val, dt, g_t, g_used, num_groups, AM_t, AK_t, AV_t,
+                                 capacity_groups, reinterpret_cast<void*>(rest), ws.end - rest, stream);
 }
 
 // ============================================================================================

@@ -62,3 +62,19 @@ def test_full_config(name):
     print(f"[full config] {name}: comparing ({time.time()-t0:.1f}s)", flush=True)
     assert_spmm_close(got, C64, absprod, RTOL[dt], name)
     print(f"[full config] {name}: ok ({time.time()-t0:.1f}s)", flush=True)
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg3"])
+def test_full_config_transposed_format(name):
+    """GroupCOO of A^T built from the format at full size.  These matrices have no repeated
+    coordinates, so the expected arrays are the oracle's conversion of the exchanged COO (the
+    identity the CPU pins establish for the oracle's own transpose)."""
+    import paper_2510_17505_amd as I
+    cfg = synth.make_config(name)
+    M, K, dt = cfg["M"], cfg["K"], cfg["a_dtype"]
+    print(f"[full config] {name}: transposed format, nnz={cfg['row'].size}", flush=True)
+    A = I.insum_coo_to_groupcoo(M, K, *coo_to_device(cfg["row"], cfg["col"], cfg["val"], dt), g=0)
+    At = I.insum_groupcoo_transpose(A)
+    del A
+    want = oracle.coo_to_groupcoo(K, M, cfg["col"], cfg["row"], synth.storage_array(cfg["val"], dt), None)
+    assert_format_equal(At.g, At.AM, At.AK, At.AV, want)

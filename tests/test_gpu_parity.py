@@ -78,6 +78,50 @@ def test_coo_to_groupcoo_bit_exact(I, M, K, nnz, g, dtype, kind):
     assert torch.equal(again.AK, got.AK) and torch.equal(again.AM, got.AM)
 
 
+@pytest.mark.parametrize("M,K,nnz,g,dtype,kind", GROUP_CASES)
+def test_groupcoo_transpose_bit_exact(I, M, K, nnz, g, dtype, kind):
+    _say(f"[groupcoo transpose] M={M} K={K} nnz~{nnz} g={g} {dtype} {kind}")
+    row, col, val = _group_case(M, K, nnz, kind, dtype, seed=nnz)
+    A = I.insum_coo_to_groupcoo(M, K, *coo_to_device(row, col, val, dtype), g=g)
+    g_o, AM, AK, AV = oracle.coo_to_groupcoo(M, K, row, col, synth.storage_array(val, dtype), g or None)
+    for g_t in (0, 3):
+        want = oracle.groupcoo_transpose(M, K, AM, AK, AV, g_t or None)
+        got = I.insum_groupcoo_transpose(A, g=g_t)
+        assert (got.M, got.K) == (K, M)
+        assert_format_equal(got.g, got.AM, got.AK, got.AV, want)
+
+
+def test_groupcoo_transpose_then_spmm_is_the_transposed_product(I):
+    M, K, N = 5000, 3000, 72
+    _say("[groupcoo transpose + spmm]")
+    row, col, val = synth.zipf_rows_coo(M, K, 1.2, 6.0, 11, "f32", "normal")
+    A = I.insum_coo_to_groupcoo(M, K, *coo_to_device(row, col, val, "f32"), g=4)
+    At = I.insum_groupcoo_transpose(A)
+    E = np.random.default_rng(3).standard_normal((M, N)).astype(np.float32)
+    D = I.insum_spmm_groupcoo(At, torch.from_numpy(E).cuda())
+    AM, AK, AV = A.AM.cpu().numpy(), A.AK.cpu().numpy(), A.AV.cpu().numpy()
+    D64 = oracle.spmm_groupcoo_transposed(M, K, N, AM, AK, AV, E)
+    absprod = oracle.spmm_groupcoo_transposed(M, K, N, AM, AK, np.abs(AV), np.abs(E))
+    assert_spmm_close(D.cpu().numpy(), D64, absprod, RTOL["f32"], "A^T E through the transposed format")
+    # no atomics on this route: the same bits every time
+    assert torch.equal(D, I.insum_spmm_groupcoo(At, torch.from_numpy(E).cuda()))
+
+
+def test_groupcoo_transpose_edge_cases(I):
+    dev = "cuda"
+    e = torch.zeros(0, dtype=torch.int32, device=dev)
+    A0 = I.insum_coo_to_groupcoo(10, 20, e, e, torch.zeros(0, device=dev), g=4)
+    At = I.insum_groupcoo_transpose(A0, g=2)
+    assert (At.M, At.K, At.G, At.g) == (20, 10, 0, 2)
+    # a caller-built format with a row index outside the matrix is reported, not followed
+    bad = I.GroupCOO(4, 6, 2, torch.tensor([0, 9], dtype=torch.int32, device=dev),
+                     torch.tensor([[1, 2], [3, 3]], dtype=torch.int32, device=dev),
+                     torch.tensor([[1.0, 2.0], [3.0, 0.0]], device=dev))
+    with pytest.raises(I.InsumError) as ex:
+        I.insum_groupcoo_transpose(bad)
+    assert ex.value.status == 2
+
+
 def test_coo_to_groupcoo_edge_cases(I):
     dev = "cuda"
     e = torch.zeros(0, dtype=torch.int32, device=dev)

@@ -83,6 +83,9 @@ def test_argument_validation_without_a_gpu():
     assert I.insum_spmm_groupcoo_workspace_bytes(1 << 20, 128, 4_600_000, 4) > 0
     assert I.insum_spmm_blockgroupcoo_workspace_bytes(8192, 512, 1760, 4, 32, 32) > 0    # room for a plan
     assert I.insum_spmm_blockgroupcoo_workspace_bytes(8192, 512, 1760, 4, 8, 8) == 0      # general kernel: none
+    tws = I.api._gt_ws
+    assert tws(1000, 2000, 500, 4) >= I.api._g_ws(2000, 2000) + 5 * 2000 * 4   # entry arrays + the conversion's own
+    assert tws(1000, 2000, 0, 4) > 0 and tws(1000, 2000, 1 << 29, 4) == 0       # G * g must stay below 2^31
 
 
 def test_conversion_argument_validation_without_a_gpu():
