@@ -204,6 +204,12 @@ def run_workload(torch, I, name, steps, warmup, peaks=None):
                 roof["frac_of_measured_peak"] = gbs / mp
                 roof["measured_peak_is"] = (f"random {row_bytes}-byte row reads over a {key} set "
                                             f"(csrc/peaks.hip), the access pattern of the gather")
+            mix = peaks.get("row_gather_with_stores_gbs", {}).get(str(row_bytes), {}).get(key) if key else None
+            if mix:
+                roof["measured_mix_peak"] = mix
+                roof["frac_of_measured_mix_peak"] = gbs / mix
+                roof["measured_mix_peak_is"] = ("the same reads with one row written (streaming, per lane group) "
+                                                "per 16 rows read: the read/write mix of this workload")
             roof["frac_of_bound"] = gbs / HBM_PEAK_GBS      # min(HBM, ALU) = HBM for a 0.5 flop/byte path
         if b_bytes <= (32 << 20):
             roof["note"] = ("B fits the 8 x 4 MiB L2: the gathers are served by the caches; bytes are "
@@ -304,6 +310,7 @@ def measured_peaks():
                        ("insum_peak_read_gbs", [ctypes.c_size_t, ctypes.c_int]),
                        ("insum_peak_random_read_gbs", [ctypes.c_size_t, ctypes.c_int]),
                        ("insum_peak_random_rows_gbs", [ctypes.c_size_t, ctypes.c_int, ctypes.c_int]),
+                       ("insum_peak_gather_store_gbs", [ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.c_int]),
                        ("insum_peak_mfma_tflops", [ctypes.c_int])):
         getattr(lib, name).restype = ctypes.c_double
         getattr(lib, name).argtypes = args
@@ -317,6 +324,9 @@ def measured_peaks():
                                  "2GiB": lib.insum_peak_random_read_gbs(2 << 30, 2)},
         "random_row_read_gbs": {str(rb): {k: lib.insum_peak_random_rows_gbs(ws, rb, 2) for k, ws in sets}
                                 for rb in (256, 512)},
+        # the same reads with one row written per 16 read (cfg3: 16 entries per row of C)
+        "row_gather_with_stores_gbs": {str(rb): {k: lib.insum_peak_gather_store_gbs(ws, rb, 16, 2) for k, ws in sets}
+                                       for rb in (256, 512)},
         "mfma_bf16_tflops": lib.insum_peak_mfma_tflops(2),
     }
 

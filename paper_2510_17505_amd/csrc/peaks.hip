@@ -9,6 +9,10 @@
 //                               offsets inside a working set               -> GB/s
 //   insum_peak_random_rows_gbs  the same with pieces of 64 ... 1024 bytes read by 4 ... 64 lanes
 //                               (the access pattern of a row gather)       -> GB/s
+//   insum_peak_gather_store_gbs the same row reads with one row written per `gathers_per_store`
+//                               reads, every lane group writing its own consecutive rows (the
+//                               read/write mix of an SpMM whose rows hold that many entries)
+//                                                                          -> GB/s (read + write)
 //   insum_peak_mfma_tflops      register-resident v_mfma_f32_32x32x16_bf16 -> TFLOP/s
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -76,6 +80,36 @@ __global__ __launch_bounds__(256) void k_random_rows(const char* __restrict__ sr
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) acc += v[u];
+    }
+    if (acc.x == 0x12345678u) sink[0] = acc.y + acc.z + acc.w;
+}
+
+// As k_random_rows, and after every `gps` reads (a multiple of 8) the group stores the running sum
+// as one more row of its own output range [group * (iters / gps), ...) of dst.
+template <int LPR>
+__global__ __launch_bounds__(256) void k_gather_store(const char* __restrict__ src, size_t pieces, int iters, int gps,
+                                                      char* __restrict__ dst, uint32_t* sink) {
+    const int sub = threadIdx.x % LPR;
+    const size_t group = ((size_t)blockIdx.x * 256 + threadIdx.x) / LPR;
+    uint32_t state = (uint32_t)group * 2654435761u + 12345u;
+    u32x4 acc = {0, 0, 0, 0};
+    char* out = dst + group * (size_t)(iters / gps) * (LPR * 16) + sub * 16;
+    int since = 0;
+    for (int i = 0; i < iters; i += 8) {
+        u32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            state = state * 1664525u + 1013904223u;
+            v[u] = *reinterpret_cast<const u32x4*>(src + ((size_t)(state >> 4) % pieces) * (LPR * 16) + sub * 16);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += v[u];
+        since += 8;
+        if (since >= gps) {
+            since = 0;
+            __builtin_nontemporal_store(acc, reinterpret_cast<u32x4*>(out));
+            out += LPR * 16;
+        }
     }
     if (acc.x == 0x12345678u) sink[0] = acc.y + acc.z + acc.w;
 }
@@ -206,6 +240,45 @@ extern "C" double insum_peak_random_rows_gbs(size_t working_set_bytes, int row_b
         if (r > 0 && gbs > best) best = gbs;
     }
     (void)hipFree(src);
+    (void)hipFree(sink);
+    return best;
+}
+
+extern "C" double insum_peak_gather_store_gbs(size_t working_set_bytes, int row_bytes, int gathers_per_store,
+                                              int repeats) {
+    Timer t;
+    char *src = nullptr, *dst = nullptr;
+    uint32_t* sink = nullptr;
+    if (working_set_bytes < (1 << 20)) working_set_bytes = 1 << 20;
+    if (row_bytes != 256 && row_bytes != 512) return -1.0;
+    const int blocks = 256 * 8, iters = 512;
+    const int gps = gathers_per_store < 8 ? 8 : gathers_per_store > iters ? iters : gathers_per_store / 8 * 8;
+    const size_t groups = (size_t)blocks * 256 / (row_bytes / 16);
+    const size_t out_bytes = groups * (size_t)(iters / gps) * row_bytes;   // rows written per launch
+    if (!t.ok || hipMalloc(&src, working_set_bytes) != hipSuccess || hipMalloc(&dst, out_bytes) != hipSuccess ||
+        hipMalloc(&sink, 4) != hipSuccess) {
+        (void)hipFree(src);
+        (void)hipFree(dst);
+        return -1.0;
+    }
+    (void)hipMemset(src, 1, working_set_bytes);
+    const size_t pieces = working_set_bytes / row_bytes;
+    double best = -1.0;
+    for (int r = 0; r < repeats + 1; ++r) {
+        (void)hipEventRecord(t.e0);
+        if (row_bytes == 256)
+            hipLaunchKernelGGL(k_gather_store<16>, dim3(blocks), dim3(256), 0, 0, (const char*)src, pieces, iters, gps, dst, sink);
+        else
+            hipLaunchKernelGGL(k_gather_store<32>, dim3(blocks), dim3(256), 0, 0, (const char*)src, pieces, iters, gps, dst, sink);
+        (void)hipEventRecord(t.e1);
+        if (hipEventSynchronize(t.e1) != hipSuccess) { best = -1.0; break; }
+        float ms = 0;
+        (void)hipEventElapsedTime(&ms, t.e0, t.e1);
+        const double gbs = ((double)blocks * 256 * iters * 16 + (double)out_bytes) / ms / 1e6;
+        if (r > 0 && gbs > best) best = gbs;
+    }
+    (void)hipFree(src);
+    (void)hipFree(dst);
     (void)hipFree(sink);
     return best;
 }
