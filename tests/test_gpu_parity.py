@@ -555,6 +555,48 @@ def test_spmm_calls_can_be_captured_in_a_hip_graph(I):
         torch.cuda.synchronize()
 
 
+def test_planned_block_spmm_and_transposed_product_in_a_hip_graph(I):
+    """The planned block SpMM with a split block row (partial tiles, arrival counters that the
+    last chunk resets) and the transposed product (its clearing pass is a kernel, not a memset)
+    under graph capture: every replay reproduces the eager result - bit for bit for the planned
+    SpMM, to summation order for the atomics of the transposed product."""
+    bM = bK = 32
+    nbr, nbc, N = 5, 1500, 256
+    row, col, val = _hub_block_coo(nbr, nbc, bM, bK, [2, 1300, 0, 30, 400], seed=9, dtype="bf16")
+    M, K = nbr * bM, nbc * bK
+    Ab = I.insum_coo_to_blockgroupcoo(M, K, *coo_to_device(row, col, val, "bf16"), bM, bK, g=4)
+    Bd = values_to_torch(synth.round_to_dtype(np.random.default_rng(0).standard_normal((K, N)), "bf16"), "bf16")
+    plan = I.insum_spmm_blockgroupcoo_plan(Ab, N)
+    assert plan is not None
+    ref = I.insum_spmm_blockgroupcoo(Ab, Bd, workspace=plan).clone()
+    r2, c2, v2 = synth.zipf_rows_coo(2000, 1500, 1.2, 8.0, seed=4, dtype="f32", values="normal")
+    A = I.insum_coo_to_groupcoo(2000, 1500, *coo_to_device(r2, c2, v2, "f32"), g=4)
+    E = torch.randn((2000, 96), device="cuda")
+    refT = I.insum_spmm_groupcoo_transposed(A, E).clone()
+    C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    D = torch.empty((1500, 96), device="cuda")
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            I.insum_spmm_blockgroupcoo(Ab, Bd, C_out=C, workspace=plan)
+            I.insum_spmm_groupcoo_transposed(A, E, D_out=D)
+    torch.cuda.current_stream().wait_stream(side)
+    scale = float(refT.abs().max())
+    for rep in range(4):
+        C.fill_(float("nan"))
+        D.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(C, ref), f"planned block SpMM, replay {rep}"
+        assert float((D - refT).abs().max()) <= 1e-5 * scale, f"transposed product, replay {rep}"
+        _ = I.insum_spmm_blockgroupcoo(Ab, Bd, workspace=plan)   # eager use of the same plan between replays
+        torch.cuda.synchronize()
+
+
 TRANSPOSED_CASES = [
     # M, K, N, nnz, g, dtype, kind, out32
     (37, 53, 9, 300, 2, "f32", "uniform", False),        # scalar path
