@@ -251,13 +251,18 @@ def run_workload(torch, I, name, steps, warmup, peaks=None):
 SPCONV = {"grid": 96, "density": 0.3, "C": 128, "M": 128, "dtype": "f16"}
 
 
-def run_spconv(torch, I, steps, warmup):
+def run_spconv(torch, I, steps, warmup, cloud="volume"):
     """Point-cloud sparse convolution (Section 6.4) on a synthetic voxel kernel map: 3x3x3
-    stencil over a 96^3 grid with 30 % of the voxels occupied, 128 -> 128 channels, fp16
-    features and weights, fp32 output.  Timed like the SpMM workloads (map already grouped)."""
+    stencil, 128 -> 128 channels, fp16 features and weights, fp32 output.  Timed like the SpMM
+    workloads (map already grouped).  cloud = "volume": a 96^3 grid with 30 % of the voxels
+    occupied independently; "surfaces": 192^3 voxels, the ones on five planes and two sphere
+    shells occupied, points numbered along the Z-curve (closer to a scanned room)."""
     import synth
     c = SPCONV
-    P, mx, my, mz, mv = synth.voxel_kernel_map(c["grid"], c["density"], seed=0, dtype=c["dtype"])
+    if cloud == "volume":
+        P, mx, my, mz, mv = synth.voxel_kernel_map(c["grid"], c["density"], seed=0, dtype=c["dtype"])
+    else:
+        P, mx, my, mz, mv = synth.surface_kernel_map(192, 5, 2, seed=0, dtype=c["dtype"])
     rng = np.random.default_rng(1)
     In = _to_device(torch, synth.round_to_dtype(rng.normal(size=(P, c["C"])).astype(np.float32), c["dtype"]),
                     c["dtype"])
@@ -288,7 +293,7 @@ def run_spconv(torch, I, steps, warmup):
     # algorithmic bytes: every map entry gathers one input row; Out is written once; map and weights
     model_bytes = S * c["C"] * 2 + P * c["M"] * 4 + slots * (4 + 4 + 2) + 4 * Map.G + 27 * c["C"] * c["M"] * 2
     tf = flops / ms / 1e9
-    return {"format": "GroupCOO along the kernel offset", "dtype": c["dtype"], "points": P, "nnz": S,
+    return {"format": "GroupCOO along the kernel offset", "cloud": cloud, "dtype": c["dtype"], "points": P, "nnz": S,
             "C": c["C"], "M": c["M"], "g": Map.g, "groups": Map.G, "ms_per_step": ms, "tflops": tf,
             "executed_tflops": executed / ms / 1e9,
             "ms_per_step_reusing_map_tables": ms_reuse,   # later layers over the same kernel map
@@ -617,7 +622,8 @@ def main():
         print(json.dumps({"width_sweep": width_sweep(torch, I, args.steps, args.warmup)}))
         return
     if args.spconv:
-        print(json.dumps({"spconv": run_spconv(torch, I, args.steps, args.warmup)}))
+        print(json.dumps({"spconv": run_spconv(torch, I, args.steps, args.warmup),
+                          "spconv_surfaces": run_spconv(torch, I, args.steps, args.warmup, cloud="surfaces")}))
         return
     if args.sweep:
         print(json.dumps({"group_size_sweep": group_size_sweep(torch, I, args.steps, args.warmup)}))

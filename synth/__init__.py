@@ -14,6 +14,7 @@ from .workloads import (  # noqa: F401
     random_coo,
     round_to_dtype,
     storage_array,
+    surface_kernel_map,
     voxel_kernel_map,
     zipf_rows_coo,
 )

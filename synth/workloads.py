@@ -182,9 +182,62 @@ def voxel_kernel_map(grid: int, density: float, seed: int, kernel: int = 3, dtyp
     voxel x and every offset z of the kernel^3 stencil whose neighbour y is occupied the map
     holds the entry (x, y, z).  Stands in for the voxelised indoor scans of Section 6.4.
     Returns (P, mx, my, mz, mv): number of points and the COO arrays of Map[x, y, z]."""
-    r_pos, r_val, _, r_perm = _streams(seed)
+    r_pos = _streams(seed)[0]
     occ = r_pos.random((grid, grid, grid)) < density
+    return _kernel_map_of(occ, seed, kernel, dtype, values, shuffle)
+
+
+def _morton_order(coords: np.ndarray) -> np.ndarray:
+    """Permutation that lists voxel coordinates [P, 3] (each below 2^21) in Z-curve order."""
+    def spread(v):   # put two zero bits between the bits of v
+        v = v.astype(np.uint64)
+        v = (v | (v << np.uint64(32))) & np.uint64(0x1F00000000FFFF)
+        v = (v | (v << np.uint64(16))) & np.uint64(0x1F0000FF0000FF)
+        v = (v | (v << np.uint64(8))) & np.uint64(0x100F00F00F00F00F)
+        v = (v | (v << np.uint64(4))) & np.uint64(0x10C30C30C30C30C3)
+        v = (v | (v << np.uint64(2))) & np.uint64(0x1249249249249249)
+        return v
+    code = spread(coords[:, 0]) | (spread(coords[:, 1]) << np.uint64(1)) | (spread(coords[:, 2]) << np.uint64(2))
+    return np.argsort(code, kind="stable")
+
+
+def surface_kernel_map(grid: int, planes: int, spheres: int, seed: int, kernel: int = 3, dtype: str = "f16",
+                       values: str = "ones", shuffle: bool = True, order: str = "morton"):
+    """The same for a point cloud that lies on surfaces, as a scanned room does (walls, floor,
+    furniture): the occupied voxels of a grid^3 volume are those within half a voxel of one of
+    `planes` random planes (the first three axis-aligned) or `spheres` random sphere shells.
+    Points are numbered along the Z-curve of their voxels (`order="morton"`, how point-cloud
+    libraries commonly sort voxels) or lexicographically (`order="lex"`): with the former,
+    consecutive points are neighbours on a surface and mostly see the same stencil offsets
+    occupied."""
+    rng = _streams(seed)[0]
+    ax = np.arange(grid, dtype=np.float32)
+    X, Y, Z = np.meshgrid(ax, ax, ax, indexing="ij")
+    occ = np.zeros((grid, grid, grid), dtype=bool)
+    for i in range(planes):
+        if i < 3:
+            n = np.zeros(3, dtype=np.float32)
+            n[i] = 1.0
+        else:
+            n = rng.standard_normal(3).astype(np.float32)
+            n /= np.linalg.norm(n)
+        c = rng.uniform(0.25 * grid, 0.75 * grid, size=3).astype(np.float32)
+        occ |= np.abs(n[0] * (X - c[0]) + n[1] * (Y - c[1]) + n[2] * (Z - c[2])) < 0.5
+    for _ in range(spheres):
+        c = rng.uniform(0.3 * grid, 0.7 * grid, size=3).astype(np.float32)
+        r = rng.uniform(0.15 * grid, 0.3 * grid)
+        occ |= np.abs(np.sqrt((X - c[0]) ** 2 + (Y - c[1]) ** 2 + (Z - c[2]) ** 2) - r) < 0.5
+    return _kernel_map_of(occ, seed, kernel, dtype, values, shuffle, order)
+
+
+def _kernel_map_of(occ: np.ndarray, seed: int, kernel: int, dtype: str, values: str, shuffle: bool,
+                   order: str = "lex"):
+    """(P, mx, my, mz, mv) of the kernel^3 stencil over the occupied voxels `occ` [grid]^3."""
+    _, r_val, _, r_perm = _streams(seed)
+    grid = occ.shape[0]
     coords = np.argwhere(occ).astype(np.int64)                     # [P, 3], lexicographic
+    if order == "morton":
+        coords = coords[_morton_order(coords)]
     P = coords.shape[0]
     half = kernel // 2
     index = -np.ones((grid + 2 * half,) * 3, dtype=np.int64)       # lookup table with a halo

@@ -292,6 +292,28 @@ def test_spconv_full_size_every_element():
     assert_spmm_close(again.cpu().numpy(), want, absprod, RTOL, "whole output, tables reused")
 
 
+@pytest.mark.parametrize("order,values", [("morton", "ones"), ("lex", "normal")])
+def test_spconv_surface_cloud(order, values):
+    """A point cloud on surfaces (planes and sphere shells), where whole 32-point tiles miss
+    most stencil offsets - the passes the output-stationary kernel skips - every element."""
+    P, mx, my, mz, mv = synth.surface_kernel_map(48, 4, 1, seed=2, dtype="f16", values=values, order=order)
+    C, M = 64, 96
+    print(f"[spconv surfaces] {order} {values}: P={P} entries={mx.size}", flush=True)
+    In = _features(P, C, 1, "f16")
+    W = synth.round_to_dtype(_features(C, M, 2, "f16", lead=27) * np.float32(0.125), "f16")
+    g, MZ, MX, MY, MV = oracle.map_to_groupcoo(P, P, 27, mx, my, mz, synth.storage_array(mv, "f16"), None)
+    Map = I.insum_map_to_groupcoo(P, P, 27, _i32(mx), _i32(my), _i32(mz), values_to_torch(mv, "f16"))
+    assert Map.g == g and np.array_equal(Map.MAPX.cpu().numpy(), MX) and np.array_equal(Map.MAPY.cpu().numpy(), MY)
+    mvf = MV.astype(np.float32)
+    want = oracle.spconv_groupcoo(P, C, M, MZ, MX, MY, mvf, In, W)
+    absprod = oracle.spconv_groupcoo(P, C, M, MZ, MX, MY, np.abs(mvf), np.abs(In), np.abs(W))
+    Ind, Wd = values_to_torch(In, "f16"), values_to_torch(W, "f16")
+    ws = torch.empty(max(1, I.insum_spconv_groupcoo_workspace_bytes(Map, C, M, Ind.dtype)), dtype=torch.uint8,
+                     device="cuda")
+    got = I.insum_spconv_groupcoo(Map, Ind, Wd, workspace=ws)
+    assert_spmm_close(got.cpu().numpy(), want, absprod, RTOL, "surface cloud")
+
+
 @pytest.mark.parametrize("values", ["ones", "normal"])
 def test_spconv_reuses_the_map_tables_across_layers(values):
     """Three layers over one kernel map: the later calls skip the table build and must still
