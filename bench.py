@@ -56,6 +56,31 @@ def _time_launches(torch, fn, steps, warmup):
     return start.elapsed_time(stop) / steps      # ms per step
 
 
+def _time_graph_replay(torch, fn, launches=20, replays=10):
+    """ms per launch when `launches` calls are captured once in a HIP graph and the graph is
+    replayed: what a launch-bound workload costs without the host's per-launch work."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        fn()                                   # warm (also: nothing is allocated during capture)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(launches):
+                fn()
+    torch.cuda.current_stream().wait_stream(side)
+    graph.replay()
+    torch.cuda.synchronize()
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(replays):
+        graph.replay()
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) / (replays * launches)
+
+
 def _per_launch_times(torch, fn, launches, flush=None):
     """Each launch timed on its own (HIP events around it); `flush`, when given, runs before
     every launch outside its timed window.  Returns (median, min) in ms."""
@@ -176,6 +201,7 @@ def run_workload(torch, I, name, steps, warmup, peaks=None):
         real_bytes = model_bytes
         stored = nblk
     ms = _time_launches(torch, fn, steps, warmup)
+    graph_ms = _time_graph_replay(torch, fn) if ms < 0.03 else None     # launch-bound sizes only
     flops = 2.0 * nnz * N
     res = {
         "workload": name, "format": "GroupCOO" if cfg["kind"] == "group" else "BlockGroupCOO",
@@ -186,6 +212,8 @@ def run_workload(torch, I, name, steps, warmup, peaks=None):
     }
     if plan_ms is not None:
         res["plan_ms"] = plan_ms
+    if graph_ms is not None:
+        res["ms_per_step_in_a_hip_graph"] = graph_ms
     b_bytes = cfg["K"] * N * sB
     if cfg["kind"] == "group":
         gbs = real_bytes / ms / 1e6
@@ -643,8 +671,9 @@ def main():
         "model_gbs": res["model_gbs"],
         "conversion_ms": res["conversion_ms"],
     }
-    if "plan_ms" in res:
-        line["plan_ms"] = res["plan_ms"]
+    for key in ("plan_ms", "ms_per_step_in_a_hip_graph"):
+        if key in res:
+            line[key] = res[key]
     if cfg["kind"] == "group":
         ws = torch.empty(I.insum_spmm_groupcoo_workspace_bytes(cfg["M"], cfg["N"], A.G, A.g), dtype=torch.uint8,
                          device="cuda")
@@ -666,7 +695,8 @@ def main():
             del keep
             torch.cuda.empty_cache()
             others[name] = {k: r[k] for k in ("format", "dtype", "nnz", "N", "g", "ms_per_step", "gflops",
-                                              "model_gbs", "roofline", "conversion_ms", "plan_ms") if k in r}
+                                              "model_gbs", "roofline", "conversion_ms", "plan_ms",
+                                              "ms_per_step_in_a_hip_graph") if k in r}
         for name in ("cfg3", "cfg2"):
             others[name + "_transposed"] = run_transposed(torch, I, name, args.steps, args.warmup)
             torch.cuda.empty_cache()
