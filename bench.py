@@ -231,7 +231,9 @@ def run_workload(torch, I, name, steps, warmup, peaks=None):
                 roof["measured_peak"] = mp
                 roof["frac_of_measured_peak"] = gbs / mp
                 roof["measured_peak_is"] = (f"random {row_bytes}-byte row reads over a {key} set "
-                                            f"(csrc/peaks.hip), the access pattern of the gather")
+                                            f"(csrc/peaks.hip), the access pattern of the gather; a "
+                                            f"microbenchmark of this run, repeatable to 1-2 %, so a ratio "
+                                            f"slightly above 1 is within its noise - `frac` is the roofline figure")
             mix = peaks.get("row_gather_with_stores_gbs", {}).get(str(row_bytes), {}).get(key) if key else None
             if mix:
                 roof["measured_mix_peak"] = mix
