@@ -78,3 +78,22 @@ def test_full_config_transposed_format(name):
     del A
     want = oracle.coo_to_groupcoo(K, M, cfg["col"], cfg["row"], synth.storage_array(cfg["val"], dt), None)
     assert_format_equal(At.g, At.AM, At.AK, At.AV, want)
+    # and both routes to A^T E at full size, every element against the oracle's transposed Einsum
+    N = cfg["N"]
+    print(f"[full config] {name}: A^T E on the GPU, two routes", flush=True)
+    g, AM, AK, AV = oracle.coo_to_groupcoo(M, K, cfg["row"], cfg["col"], synth.storage_array(cfg["val"], dt), None)
+    av = to_f32(AV, dt)
+    E = synth.round_to_dtype(np.random.default_rng(5).standard_normal((M, N)).astype(np.float32), dt)
+    Ed = values_to_torch(E, dt)
+    through_copy = I.insum_spmm_groupcoo(At, Ed).float().cpu().numpy()
+    del At
+    A = I.insum_coo_to_groupcoo(M, K, *coo_to_device(cfg["row"], cfg["col"], cfg["val"], dt), g=0)
+    with_atomics = I.insum_spmm_groupcoo_transposed(A, Ed).float().cpu().numpy()
+    del A, Ed
+    print(f"[full config] {name}: oracle A^T E", flush=True)
+    D64 = oracle.spmm_groupcoo_transposed(M, K, N, AM, AK, av, E)
+    absprod = oracle.spmm_groupcoo_transposed(M, K, N, AM, AK, np.abs(av), np.abs(E))
+    assert_spmm_close(through_copy, D64, absprod, RTOL[dt], name + " through the transposed format",
+                      out_dtype=dt if dt != "f32" else None)
+    assert_spmm_close(with_atomics, D64, absprod, RTOL[dt], name + " with atomics",
+                      out_dtype=dt if dt != "f32" else None)
