@@ -59,7 +59,7 @@ int32_t insum_default_group_size(int64_t S, int64_t n);
 
 /* F(g) = (g + 1) * sum_i ceil(occ_i / g): the number of indirect accesses (one scatter
  * per group through AM, g gathers per group through AK).  `occ` is a host array of n
- * row occupancies.  Returns -1 for invalid arguments. */
+ * row occupancies.  Returns -1 for invalid arguments and when F(g) does not fit 64 bits. */
 int64_t insum_indirect_access_cost(int64_t n, const int64_t* occ, int32_t g);
 
 /* The group sizes Section 4.2 considers for a matrix with S stored entries in n rows: the
@@ -218,6 +218,7 @@ size_t insum_spmm_groupcoo_workspace_bytes(int64_t M, int64_t N, int64_t G, int3
 /*
  * C = A * B (accumulate == 0) or C += A * B (accumulate != 0), A given in GroupCOO.
  *
+ *   M, K, N < 2^31, G < 2^40 (else INSUM_ERR_INVALID_ARG).
  *   AM, AK, AV  device; layout as produced by insum_coo_to_groupcoo.  AM must be
  *               non-decreasing, 0 <= AM[p] < M, 0 <= AK[p,q] < K (not checked).
  *   a_dt, b_dt, c_dt  supported: a_dt == b_dt in {F32, F16, BF16}; c_dt == b_dt or F32.

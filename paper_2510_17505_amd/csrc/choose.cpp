@@ -47,6 +47,7 @@ extern "C" int32_t insum_group_size_candidates(int64_t S, int64_t n, int32_t* ou
 
 extern "C" size_t insum_choose_group_size_workspace_bytes(int64_t M, int64_t N, int64_t nnz, insum_dtype dt) {
     if (M < 0 || N < 0 || nnz < 0 || !dtype_valid(dt)) return 0;
+    if (M >= (1LL << 31) || N >= (1LL << 31) || nnz >= (1LL << 31)) return 0;   // beyond what the conversion accepts
     int32_t cand[3];
     const int32_t nc = insum_group_size_candidates(nnz, M, cand);
     size_t conv = insum_coo_to_groupcoo_workspace_bytes(M, nnz), spmm = 0, am = 0, ak = 0;

@@ -692,7 +692,7 @@ insum_status transposed_entries(const TransposeBuffers& t, int64_t slots, int32_
 }  // namespace
 
 extern "C" size_t insum_groupcoo_transpose_workspace_bytes(int64_t M, int64_t K, int64_t G, int32_t g) {
-    if (M < 0 || K < 0 || G < 0 || g <= 0 || G * (int64_t)g >= (1LL << 31)) return 0;
+    if (M < 0 || K < 0 || G < 0 || g <= 0 || G >= (1LL << 31) || G * (int64_t)g >= (1LL << 31)) return 0;
     const int64_t slots = G * (int64_t)g;
     return transpose_front_bytes(slots) + insum_coo_to_groupcoo_workspace_bytes(K, slots);
 }
@@ -704,7 +704,8 @@ extern "C" insum_status insum_groupcoo_transpose(int64_t M, int64_t K, int64_t G
                                                  int64_t capacity_groups, void* workspace,
                                                  size_t workspace_bytes, void* stream) {
     if (M < 0 || K < 0 || G < 0 || g <= 0 || g_t < 0 || !g_used || !num_groups) return INSUM_ERR_INVALID_ARG;
-    if (M >= (1LL << 31) || K >= (1LL << 31) || G * (int64_t)g >= (1LL << 31)) return INSUM_ERR_INVALID_ARG;
+    if (M >= (1LL << 31) || K >= (1LL << 31) || G >= (1LL << 31) || G * (int64_t)g >= (1LL << 31))
+        return INSUM_ERR_INVALID_ARG;
     if (!dtype_valid(dt)) return INSUM_ERR_INVALID_ARG;
     if (G > 0 && (!AM || !AK || !AV)) return INSUM_ERR_INVALID_ARG;
     const int64_t slots = G * (int64_t)g;

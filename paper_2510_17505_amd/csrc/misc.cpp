@@ -35,10 +35,11 @@ extern "C" int32_t insum_default_group_size(int64_t S, int64_t n) {
 
 extern "C" int64_t insum_indirect_access_cost(int64_t n, const int64_t* occ, int32_t g) {
     if (n < 0 || g <= 0 || (n > 0 && !occ)) return -1;
-    int64_t groups = 0;
+    unsigned __int128 groups = 0;   // n * 2^63 at most: no overflow
     for (int64_t i = 0; i < n; ++i) {
         if (occ[i] < 0) return -1;
-        groups += occ[i] / g + (occ[i] % g != 0);
+        groups += (uint64_t)(occ[i] / g + (occ[i] % g != 0));
     }
-    return groups * ((int64_t)g + 1);
+    if (groups > (unsigned __int128)INT64_MAX / ((uint64_t)g + 1)) return -1;   // F(g) does not fit 64 bits
+    return (int64_t)(groups * ((uint64_t)g + 1));
 }

@@ -622,8 +622,10 @@ OsLayout os_layout(int64_t X, int64_t Z, int64_t C, int64_t M, int64_t slots) {
 // most of its passes would be empty and the scatter kernel is used.
 bool os_shape_ok(int64_t X, int64_t Z, int64_t C, int64_t M, int64_t slots, insum_dtype dt) {
     // (row offsets into In are 32-bit element counts: checked by the caller, which knows Y and ld_in)
-    return dt != INSUM_F32 && C % 8 == 0 && C >= 8 && C <= 256 && X > 0 && Z > 0 && M > 0 &&
-           slots * 16 >= X * Z && slots < (1LL << 31) && Z * (ceil_div(X, 512) * 512) < (1LL << 38) &&
+    if (dt == INSUM_F32 || C % 8 != 0 || C < 8 || C > 256 || X <= 0 || Z <= 0 || M <= 0) return false;
+    // sizes first, so that the products below stay far inside 64 bits
+    if (X >= (1LL << 31) || Z >= (1LL << 20) || M >= (1LL << 24) || slots >= (1LL << 31)) return false;
+    return slots * 16 >= X * Z && Z * (ceil_div(X, 512) * 512) < (1LL << 38) &&
            Z * (ceil_div(M, 128) * 128) * 256 < (1LL << 38) &&
            ceil_div(X, 128) * ceil_div(M, 64) + 8 * ceil_div(M, 64) < (1LL << 31);
 }
@@ -698,6 +700,7 @@ using namespace insum;
 extern "C" size_t insum_spconv_groupcoo_workspace_bytes(int64_t X, int64_t Z, int64_t C, int64_t M,
                                                         int64_t G, int32_t g, insum_dtype dt) {
     if (X < 0 || Z < 0 || C < 0 || M < 0 || G < 0 || g <= 0 || !dtype_valid(dt)) return 0;
+    if (G >= (1LL << 31)) return 0;   // (also keeps G * g inside 64 bits)
     const int64_t slots = G * (int64_t)g;
     if (!os_shape_ok(X, Z, C, M, slots, dt)) return 0;
     return os_layout(X, Z, C, M, slots).bytes;
@@ -714,7 +717,7 @@ extern "C" insum_status insum_spconv_groupcoo(int64_t X, int64_t Y, int64_t Z, i
     if (X >= (1LL << 31) || Y >= (1LL << 31) || Z >= (1LL << 31) || C >= (1LL << 31) || M >= (1LL << 31))
         return INSUM_ERR_INVALID_ARG;
     if (!dtype_valid(dt) || ld_in < C || ld_out < M) return INSUM_ERR_INVALID_ARG;
-    if (G * (int64_t)g >= (1LL << 40)) return INSUM_ERR_INVALID_ARG;
+    if (G >= (1LL << 31) || G * (int64_t)g >= (1LL << 40)) return INSUM_ERR_INVALID_ARG;
     if (X > 0 && M > 0 && !Out) return INSUM_ERR_INVALID_ARG;
     if (G > 0 && (!MAPZ || !MAPX || !MAPY || !MAPV)) return INSUM_ERR_INVALID_ARG;
     if (G > 0 && C > 0 && M > 0 && (!In || !W)) return INSUM_ERR_INVALID_ARG;

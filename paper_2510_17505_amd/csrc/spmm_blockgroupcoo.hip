@@ -800,7 +800,8 @@ using namespace insum;
 extern "C" size_t insum_spmm_blockgroupcoo_workspace_bytes(int64_t M, int64_t N, int64_t G, int32_t g,
                                                            int32_t bM, int32_t bK) {
     if (M <= 0 || N <= 0 || G <= 0 || g <= 0 || bM <= 0 || bK <= 0 || M % bM) return 0;
-    if (!mfma_shape(M, N, bM, bK) || G >= (1LL << 31)) return 0;  // the general kernel takes no plan
+    if (M >= (1LL << 31) || N >= (1LL << 31) || G >= (1LL << 31)) return 0;   // beyond what the SpMM accepts
+    if (!mfma_shape(M, N, bM, bK)) return 0;  // the general kernel takes no plan
     return plan_layout(M, N, G, g, bM).total;
 }
 

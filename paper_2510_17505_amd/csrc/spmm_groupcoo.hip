@@ -471,9 +471,9 @@ struct Plan {
     int64_t col_tiles, groups_per_run, runs;
 };
 
-int next_pow2(int64_t x) {
+int next_pow2(int64_t x) {   // smallest power of two >= x, at most 2^30
     int p = 1;
-    while (p < x) p <<= 1;
+    while (p < x && p < (1 << 30)) p <<= 1;
     return p;
 }
 
@@ -546,6 +546,7 @@ using namespace insum;
 extern "C" size_t insum_spmm_groupcoo_workspace_bytes(int64_t M, int64_t N, int64_t G, int32_t g) {
     (void)M;
     if (N <= 0 || G <= 0 || g <= 0) return 256;
+    if (N >= (1LL << 31) || G >= (1LL << 40)) return 0;   // beyond what the SpMM accepts
     int64_t runs = 0;
     for (int es : {2, 4})
         for (bool vec : {false, true}) runs = std::max(runs, make_plan(N, G, g, es, vec).runs);
@@ -608,7 +609,7 @@ insum_status check_spmm_groupcoo_args(int64_t M, int64_t K, int64_t N, int64_t G
                                       insum_dtype c_dt, bool& nothing_to_do) {
     nothing_to_do = false;
     if (M < 0 || K < 0 || N < 0 || G < 0 || g <= 0) return INSUM_ERR_INVALID_ARG;
-    if (M >= (1LL << 31) || K >= (1LL << 31) || N >= (1LL << 31)) return INSUM_ERR_INVALID_ARG;
+    if (M >= (1LL << 31) || K >= (1LL << 31) || N >= (1LL << 31) || G >= (1LL << 40)) return INSUM_ERR_INVALID_ARG;
     if (!dtype_valid(a_dt) || !dtype_valid(b_dt) || !dtype_valid(c_dt)) return INSUM_ERR_INVALID_ARG;
     if (a_dt != b_dt || (c_dt != b_dt && c_dt != INSUM_F32)) return INSUM_ERR_UNSUPPORTED;
     if (ldb < N || ldc < N) return INSUM_ERR_INVALID_ARG;
