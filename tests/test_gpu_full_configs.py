@@ -97,3 +97,37 @@ def test_full_config_transposed_format(name):
                       out_dtype=dt if dt != "f32" else None)
     assert_spmm_close(with_atomics, D64, absprod, RTOL[dt], name + " with atomics",
                       out_dtype=dt if dt != "f32" else None)
+
+
+def test_more_than_2_to_31_slots():
+    """Maximum sizes: a caller-built GroupCOO matrix with 2^31 + 192 slots (the conversion takes
+    fewer than 2^31 entries, the SpMM any G < 2^40), so that slot numbers pass the range of 32-bit
+    integers inside the kernel.  Values are multiples of 1/8 in [-1, 1]; every element of C
+    against the oracle."""
+    import psutil
+    import paper_2510_17505_amd as I
+    free, _ = torch.cuda.mem_get_info()
+    if free < (40 << 30) or psutil.virtual_memory().available < (64 << 30):
+        pytest.skip("needs 40 GB of device memory and 64 GB of host memory")
+    g, G = 64, (1 << 25) + 3
+    M, K, N = 1 << 20, 4096, 8
+    print(f"[max sizes] G={G} g={g}: {G * g} slots, generating", flush=True)
+    rng = np.random.default_rng(0)
+    AM = (np.arange(G, dtype=np.int64) * M // G).astype(np.int32)
+    AK = rng.integers(0, K, size=(G, g), dtype=np.int32)
+    AV = rng.integers(-8, 9, size=(G, g), dtype=np.int8).astype(np.float16) / np.float16(8)
+    B = synth.round_to_dtype(rng.standard_normal((K, N)).astype(np.float32), "f16")
+    print("[max sizes] SpMM on the GPU", flush=True)
+    A = I.GroupCOO(M, K, g, torch.from_numpy(AM).cuda(), torch.from_numpy(AK).cuda(), torch.from_numpy(AV).cuda())
+    C = I.insum_spmm_groupcoo(A, values_to_torch(B, "f16"), out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    got = C.cpu().numpy()
+    del A, C
+    torch.cuda.empty_cache()
+    print("[max sizes] oracle", flush=True)
+    av = AV.astype(np.float32)
+    del AV
+    C64 = oracle.spmm_groupcoo(M, K, N, AM, AK, av, B)
+    np.abs(av, out=av)
+    absprod = oracle.spmm_groupcoo(M, K, N, AM, AK, av, np.abs(B))
+    assert_spmm_close(got, C64, absprod, RTOL["f16"], "2^31 + 192 slots")
