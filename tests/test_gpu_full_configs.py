@@ -131,3 +131,38 @@ def test_more_than_2_to_31_slots():
     np.abs(av, out=av)
     absprod = oracle.spmm_groupcoo(M, K, N, AM, AK, av, np.abs(B))
     assert_spmm_close(got, C64, absprod, RTOL["f16"], "2^31 + 192 slots")
+
+
+def test_block_format_with_more_than_2_to_31_values():
+    """Maximum sizes for the block kernel: 524 292 blocks of 64 x 64 = 2^31 + 16 384 stored values,
+    so that element offsets into AV pass the range of 32-bit integers (DMA sources, chunk bases).
+    Values are multiples of 1/4 (exact in bf16); with and without a work plan, every element."""
+    import psutil
+    import paper_2510_17505_amd as I
+    free, _ = torch.cuda.mem_get_info()
+    if free < (24 << 30) or psutil.virtual_memory().available < (48 << 30):
+        pytest.skip("needs 24 GB of device memory and 48 GB of host memory")
+    bM = bK = 64
+    g, nbr, per_row, nbc = 4, 8192, 64, 1024
+    G = nbr * per_row // g + 1                       # one group more than 2^31 values
+    M, K, N = (nbr + 1) * bM, nbc * bK, 16
+    rng = np.random.default_rng(0)
+    AM = np.concatenate([np.repeat(np.arange(nbr, dtype=np.int32), per_row // g), np.array([nbr], dtype=np.int32)])
+    cols = np.sort(rng.permuted(np.tile(np.arange(nbc, dtype=np.int32), (nbr + 1, 1)), axis=1)[:, :per_row], axis=1)
+    AK = np.concatenate([cols[:nbr].reshape(-1, g), cols[nbr, :g].reshape(1, g)])   # ascending inside a block row
+    print(f"[max sizes] block format: {G * g} blocks, {G * g * bM * bK} values", flush=True)
+    AVf = rng.integers(-4, 5, size=(G, g, bM, bK), dtype=np.int8).astype(np.float32) / 4
+    B = synth.round_to_dtype(rng.standard_normal((K, N)).astype(np.float32), "bf16")
+    A = I.BlockGroupCOO(M, K, bM, bK, g, torch.from_numpy(AM).cuda(), torch.from_numpy(AK).cuda(),
+                        values_to_torch(AVf, "bf16"))
+    Bd = values_to_torch(B, "bf16")
+    planned = I.insum_spmm_blockgroupcoo(A, Bd, out_dtype=torch.float32).cpu().numpy()
+    unplanned = I.insum_spmm_blockgroupcoo(A, Bd, out_dtype=torch.float32, plan=False).cpu().numpy()
+    del A
+    torch.cuda.empty_cache()
+    print("[max sizes] block format: oracle", flush=True)
+    C64 = oracle.spmm_blockgroupcoo(M, K, N, bM, bK, AM, AK, AVf, B)
+    np.abs(AVf, out=AVf)
+    absprod = oracle.spmm_blockgroupcoo(M, K, N, bM, bK, AM, AK, AVf, np.abs(B))
+    assert_spmm_close(planned, C64, absprod, RTOL["bf16"], "2^31 + 16384 values, planned")
+    assert_spmm_close(unplanned, C64, absprod, RTOL["bf16"], "2^31 + 16384 values, block rows in index order")
