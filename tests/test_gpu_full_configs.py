@@ -166,3 +166,36 @@ def test_block_format_with_more_than_2_to_31_values():
     absprod = oracle.spmm_blockgroupcoo(M, K, N, bM, bK, AM, AK, AVf, np.abs(B))
     assert_spmm_close(planned, C64, absprod, RTOL["bf16"], "2^31 + 16384 values, planned")
     assert_spmm_close(unplanned, C64, absprod, RTOL["bf16"], "2^31 + 16384 values, block rows in index order")
+
+
+def test_output_with_more_than_2_to_31_elements():
+    """Maximum sizes: C has 2^21 x 1032 = 2^31 + 2^24 elements, so element offsets into C pass
+    the range of 32-bit integers.  The first and last 500 rows and 2 000 random rows are compared
+    with the oracle (run on those rows' entries); rows without entries must be zero everywhere."""
+    import paper_2510_17505_amd as I
+    free, _ = torch.cuda.mem_get_info()
+    if free < (16 << 30):
+        pytest.skip("needs 16 GB of device memory")
+    M, K, N, nnz = 1 << 21, 2048, 1032, 4_000_000
+    rng = np.random.default_rng(0)
+    row = rng.integers(0, M, nnz).astype(np.int32)
+    col = rng.integers(0, K, nnz).astype(np.int32)
+    val = synth.round_to_dtype(rng.standard_normal(nnz).astype(np.float32), "f16")
+    B = synth.round_to_dtype(rng.standard_normal((K, N)).astype(np.float32), "f16")
+    print(f"[max sizes] C with {M * N} elements", flush=True)
+    A = I.insum_coo_to_groupcoo(M, K, *coo_to_device(row, col, val, "f16"), g=4)
+    C = I.insum_spmm_groupcoo(A, values_to_torch(B, "f16"))
+    torch.cuda.synchronize()
+    sample = np.unique(np.concatenate([np.arange(500), np.arange(M - 500, M), rng.integers(0, M, 2000)]))
+    keep = np.isin(row, sample)
+    remap = -np.ones(M, dtype=np.int64)
+    remap[sample] = np.arange(sample.size)
+    g, AM, AK, AV = oracle.coo_to_groupcoo(sample.size, K, remap[row[keep]].astype(np.int32), col[keep],
+                                           synth.storage_array(val[keep], "f16"), 4)
+    av = to_f32(AV, "f16")
+    C64 = oracle.spmm_groupcoo(sample.size, K, N, AM, AK, av, B)
+    absprod = oracle.spmm_groupcoo(sample.size, K, N, AM, AK, np.abs(av), np.abs(B))
+    got = C[torch.from_numpy(sample).cuda()].float().cpu().numpy()
+    assert_spmm_close(got, C64, absprod, RTOL["f16"], "sampled rows", out_dtype="f16")
+    empty = torch.from_numpy(np.bincount(row, minlength=M) == 0).cuda()
+    assert bool((C[empty] == 0).all()) and not bool(torch.isnan(C).any())
