@@ -199,3 +199,25 @@ def test_output_with_more_than_2_to_31_elements():
     assert_spmm_close(got, C64, absprod, RTOL["f16"], "sampled rows", out_dtype="f16")
     empty = torch.from_numpy(np.bincount(row, minlength=M) == 0).cuda()
     assert bool((C[empty] == 0).all()) and not bool(torch.isnan(C).any())
+
+
+def test_conversion_at_the_largest_matrix_shape():
+    """Maximum sizes: M = K = 2^31 - 1 (62-bit sort keys, per-row arrays of 2^31 entries) with a
+    few thousand entries, some in the first and last rows and columns: bit-exact."""
+    import psutil
+    import paper_2510_17505_amd as I
+    free, _ = torch.cuda.mem_get_info()
+    if free < (40 << 30) or psutil.virtual_memory().available < (40 << 30):
+        pytest.skip("needs 40 GB of device memory and 40 GB of host memory")
+    M = K = (1 << 31) - 1
+    nnz = 5000
+    rng = np.random.default_rng(0)
+    row = rng.integers(0, M, nnz).astype(np.int32)
+    col = rng.integers(0, K, nnz).astype(np.int32)
+    row[:50], row[50:100], row[100:140] = M - 1, 0, M - 2
+    col[:25], col[50:75] = K - 1, 0
+    val = rng.standard_normal(nnz).astype(np.float32)
+    print(f"[max sizes] conversion with M = K = {M}", flush=True)
+    A = I.insum_coo_to_groupcoo(M, K, *coo_to_device(row, col, val, "f32"), g=4)
+    want = oracle.coo_to_groupcoo(M, K, row, col, val, 4)
+    assert_format_equal(A.g, A.AM, A.AK, A.AV, want)
