@@ -221,3 +221,48 @@ def test_conversion_at_the_largest_matrix_shape():
     A = I.insum_coo_to_groupcoo(M, K, *coo_to_device(row, col, val, "f32"), g=4)
     want = oracle.coo_to_groupcoo(M, K, row, col, val, 4)
     assert_format_equal(A.g, A.AM, A.AK, A.AV, want)
+
+
+@pytest.mark.parametrize("M,K", [((1 << 31) - 32, 128), (128, (1 << 31) - 32)])
+def test_block_conversion_at_the_largest_extents(M, K):
+    """Maximum sizes: 2^26 - 1 block rows (or block columns) of 32 x 32 blocks, a few hundred
+    stored blocks that include the first and the last block row and column: bit-exact.  (The
+    other extent is small because the oracle keeps a table over the whole block grid.)"""
+    import paper_2510_17505_amd as I
+    bM = bK = 32
+    rng = np.random.default_rng(M % 1000)
+    nbr, nbc = M // bM, K // bK
+    br, bc = rng.integers(0, nbr, 300), rng.integers(0, nbc, 300)
+    br[:20], br[20:40] = nbr - 1, 0
+    bc[:10], bc[20:30] = nbc - 1, 0
+    key = np.unique(br.astype(np.int64) * nbc + bc)
+    rows, cols = [], []
+    for r, c in zip(key // nbc, key % nbc):
+        pos = rng.choice(bM * bK, size=7, replace=False)
+        rows.append(r * bM + pos // bK)
+        cols.append(c * bK + pos % bK)
+    row, col = np.concatenate(rows).astype(np.int32), np.concatenate(cols).astype(np.int32)
+    val = synth.round_to_dtype(rng.standard_normal(row.size).astype(np.float32), "bf16")
+    perm = rng.permutation(row.size)
+    row, col, val = row[perm], col[perm], val[perm]
+    print(f"[max sizes] block conversion, M={M} K={K}", flush=True)
+    want = oracle.coo_to_blockgroupcoo(M, K, row, col, synth.storage_array(val, "bf16"), bM, bK, None)
+    A = I.insum_coo_to_blockgroupcoo(M, K, *coo_to_device(row, col, val, "bf16"), bM, bK, g=0)
+    assert_format_equal(A.g, A.AM, A.AK, A.AV, want)
+
+
+def test_map_conversion_at_the_largest_point_count():
+    """Maximum sizes: a kernel map over 2^31 - 1 points (keys z * X + x of 36 bits): bit-exact."""
+    import paper_2510_17505_amd as I
+    rng = np.random.default_rng(3)
+    X, n = (1 << 31) - 1, 4000
+    mx, my = rng.integers(0, X, n).astype(np.int32), rng.integers(0, X, n).astype(np.int32)
+    mz = rng.integers(0, 27, n).astype(np.int32)
+    mx[:30], mx[30:60], mz[:15] = X - 1, 0, 26
+    mv = synth.round_to_dtype(rng.standard_normal(n).astype(np.float32), "f16")
+    g, MZ, MX, MY, MV = oracle.map_to_groupcoo(X, X, 27, mx, my, mz, synth.storage_array(mv, "f16"), None)
+    Map = I.insum_map_to_groupcoo(X, X, 27, torch.from_numpy(mx).cuda(), torch.from_numpy(my).cuda(),
+                                  torch.from_numpy(mz).cuda(), values_to_torch(mv, "f16"))
+    assert Map.g == g and np.array_equal(Map.MAPZ.cpu().numpy(), MZ)
+    assert np.array_equal(Map.MAPX.cpu().numpy(), MX) and np.array_equal(Map.MAPY.cpu().numpy(), MY)
+    assert np.array_equal(Map.MAPV.cpu().numpy().view(np.uint16), MV.view(np.uint16))
