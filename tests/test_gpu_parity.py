@@ -597,6 +597,38 @@ def test_planned_block_spmm_and_transposed_product_in_a_hip_graph(I):
         torch.cuda.synchronize()
 
 
+def test_calls_on_two_streams_do_not_disturb_each_other(I):
+    """The SpMM entry points keep no state outside their arguments: calls issued on two streams,
+    each with its own workspace (and its own plan for the block kernel), may overlap on the GPU and
+    still give the bits of the same calls made one after the other."""
+    M, K, N = 3000, 2500, 256
+    r1, c1, v1 = synth.zipf_rows_coo(M, K, 1.2, 10.0, seed=1, dtype="f32", values="normal")
+    A1 = I.insum_coo_to_groupcoo(M, K, *coo_to_device(r1, c1, v1, "f32"), g=4)
+    B1 = torch.randn((K, N), device="cuda")
+    bM = bK = 32
+    rb, cb, vb = _hub_block_coo(6, 900, bM, bK, [5, 700, 1, 30, 0, 250], seed=2, dtype="bf16")
+    Mb, Kb = 6 * bM, 900 * bK
+    A2 = I.insum_coo_to_blockgroupcoo(Mb, Kb, *coo_to_device(rb, cb, vb, "bf16"), bM, bK, g=4)
+    B2 = torch.randn((Kb, N), device="cuda").bfloat16()
+    ws = [torch.empty(I.insum_spmm_groupcoo_workspace_bytes(M, N, A1.G, A1.g), dtype=torch.uint8, device="cuda")
+          for _ in range(2)]
+    plans = [I.insum_spmm_blockgroupcoo_plan(A2, N) for _ in range(2)]
+    ref1 = I.insum_spmm_groupcoo(A1, B1, workspace=ws[0]).clone()
+    ref2 = I.insum_spmm_blockgroupcoo(A2, B2, workspace=plans[0]).clone()
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = [[], []]
+    for rep in range(6):
+        for i, st in enumerate(streams):
+            with torch.cuda.stream(st):
+                outs[i].append((I.insum_spmm_groupcoo(A1, B1, workspace=ws[i]).clone(),
+                                I.insum_spmm_blockgroupcoo(A2, B2, workspace=plans[i]).clone()))
+    torch.cuda.synchronize()
+    for i in range(2):
+        for c1_, c2_ in outs[i]:
+            assert torch.equal(c1_, ref1) and torch.equal(c2_, ref2)
+
+
 TRANSPOSED_CASES = [
     # M, K, N, nnz, g, dtype, kind, out32
     (37, 53, 9, 300, 2, "f32", "uniform", False),        # scalar path
