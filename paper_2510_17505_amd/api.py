@@ -226,20 +226,25 @@ def insum_coo_to_groupcoo(M: int, K: int, row, col, val, g: int = 0) -> GroupCOO
 
 
 def insum_groupcoo_transpose(A: GroupCOO, g: int = 0) -> GroupCOO:
-    """GroupCOO of A^T built on the device from the GroupCOO of A (count call, then fill call)."""
+    """GroupCOO of A^T built on the device from the GroupCOO of A, in one fill call: the outputs
+    are sized by the bounds of insum.h for the largest group size the call can choose (the number
+    of entries, which decides the default group size, is at most the number of slots), and the
+    result is a view of the first G groups."""
     dev = A.AV.device
+    slots = A.G * A.g
     ws = torch.empty(max(1, int(_gt_ws(A.M, A.K, A.G, A.g))), dtype=torch.uint8, device=dev)
     g_used, G, entries = _i32(0), _i64(0), _i64(0)
-    args = (A.M, A.K, A.G, A.g, _ptr(A.AM), _ptr(A.AK), _ptr(A.AV), _DTYPE[A.AV.dtype], int(g),
-            C.addressof(g_used), C.addressof(G), C.addressof(entries))
-    _check(_gt(*args, 0, 0, 0, 0, _ptr(ws), ws.numel(), _stream()), "insum_groupcoo_transpose(count)")
-    AM = torch.empty(G.value, dtype=torch.int32, device=dev)
-    AK = torch.empty((G.value, g_used.value), dtype=torch.int32, device=dev)
-    AV = torch.empty((G.value, g_used.value), dtype=A.AV.dtype, device=dev)
-    if G.value:
-        _check(_gt(*args, _ptr(AM), _ptr(AK), _ptr(AV), G.value, _ptr(ws), ws.numel(), _stream()),
-               "insum_groupcoo_transpose(fill)")
-    return GroupCOO(A.K, A.M, g_used.value, AM, AK, AV)
+    g_max = int(g) if g else insum_default_group_size(slots, A.K)
+    cap = slots + min(A.K, slots)                       # groups: entries/g + min(K, entries), any g >= 1
+    AM = torch.empty(cap, dtype=torch.int32, device=dev)
+    flat = slots + min(A.K, slots) * g_max              # slots of the result: cap(g) * g for g <= g_max
+    AK = torch.empty(flat, dtype=torch.int32, device=dev)
+    AV = torch.empty(flat, dtype=A.AV.dtype, device=dev)
+    _check(_gt(A.M, A.K, A.G, A.g, _ptr(A.AM), _ptr(A.AK), _ptr(A.AV), _DTYPE[A.AV.dtype], int(g),
+               C.addressof(g_used), C.addressof(G), C.addressof(entries), _ptr(AM), _ptr(AK), _ptr(AV),
+               cap, _ptr(ws), ws.numel(), _stream()), "insum_groupcoo_transpose")
+    n, gu = G.value, g_used.value
+    return GroupCOO(A.K, A.M, gu, AM[:n], AK[:n * gu].view(n, gu), AV[:n * gu].view(n, gu))
 
 
 def insum_coo_to_blockgroupcoo(M: int, K: int, row, col, val, bM: int, bK: int, g: int = 0) -> BlockGroupCOO:
