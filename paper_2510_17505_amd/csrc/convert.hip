@@ -19,6 +19,10 @@
 // way: key = z*X + x, the sort carries (y, value bits) packed in 64 bits, and the offsets play
 // the part of the rows.
 //
+// The GroupCOO of the transposed matrix (insum_groupcoo_transpose) reuses all of this: the slots
+// that hold entries are numbered with a prefix sum and written out as COO with row and column
+// exchanged, and the conversion above groups them.
+//
 // The device-wide stable radix sort and the prefix sums are in sort_scan.h; keys are 32 bits
 // wide when the largest possible key fits (it does for every block workload here) and 64 bits
 // otherwise, and only the digits such a key can have are sorted.

@@ -9,7 +9,9 @@
 //     wavefront keeps its bM x 64 fp32 accumulator in registers for the whole block row,
 //     so C is written exactly once and never needs atomics.  The groups of a block row are
 //     consecutive in AM (non-decreasing); the workgroup finds them by binary search.  A
-//     block row without groups just writes zeros.
+//     block row without groups just writes zeros.  (With a work plan - further down - a
+//     block row much longer than the others is cut into chunks for several workgroups,
+//     whose fp32 tiles the last one to finish adds in chunk order.)
 //   * Work is cut into steps: one stored block (padding blocks repeat the previous block
 //     column and are skipped) x one k-chunk of KC rows.  Per step the gathered B tile
 //     (KC x NT) and the A chunk (bM x KC) are copied global -> LDS by the DMA path
